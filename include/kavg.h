@@ -1,0 +1,157 @@
+/*
+ * kavg.h -- C boundary of the M-AVG hot path (K-step averaging SGD with block
+ * momentum) for one AMD MI355X (gfx950).
+ *
+ * The library runs Algorithm 1 of the paper (Section 2, "M-AVG Algorithm") on an
+ * MLP with ReLU hidden layers and softmax cross-entropy, the instance of the
+ * objective F(w) = (1/n) sum_i loss(y_i, f(x_i, w)) stated in Section 2:
+ *
+ *   every round n:   each of P learners starts from the global model w~_n and
+ *                    takes K minibatch-SGD steps  w <- w - (lr/B) sum_s grad F(w; xi_s)
+ *                    on its own replica                       (kavg_local_steps)
+ *                    a = (1/P) sum_j w^j;  d = a - w~_n;  v <- mu v + d;
+ *                    w~_{n+1} = w~_n + v;  every w^j <- w~_{n+1}   (kavg_meta_update)
+ *
+ * All P replicas live in device memory of one GPU; every step runs in HIP
+ * kernels of this library.  There is no CPU fallback.
+ *
+ * Conventions
+ *  - Every function returns an int status (KAVG_OK = 0).  Nothing throws,
+ *    aborts or prints.  kavg_last_error() returns a text for the last failure
+ *    on that context (owned by the context, valid until the next call on it).
+ *  - "dev" pointers are device memory of the current HIP device, "host"
+ *    pointers are ordinary host memory.  The library never allocates or frees
+ *    device memory: the caller passes one workspace block and keeps it, the
+ *    data set and any index array alive until kavg_destroy.
+ *  - Work is enqueued on the HIP stream given to kavg_init (NULL = the default
+ *    stream).  kavg_local_steps and kavg_meta_update return without waiting;
+ *    the functions that copy to the host wait for the stream.
+ *  - A context is not thread safe.
+ *
+ * Flat parameter layout (what "n floats" means everywhere): for l = 1..L the
+ * weight matrix W_l row-major [d_l][d_{l-1}] (output-major), then the bias
+ * b_l [d_l].  n = sum_l (d_l d_{l-1} + d_l).
+ *
+ * dtype
+ *  KAVG_FP32: every tensor and every product in fp32.
+ *  KAVG_BF16: operands of every matrix product are bf16 (round to nearest
+ *    even): the data set (given as bf16), a bf16 shadow of each replica's
+ *    weights (refreshed by every update and by the meta step), the stored
+ *    hidden activations and the back-propagated dZ_l.  Accumulation is fp32;
+ *    logits, softmax, loss, biases, master parameters, the SGD update and the
+ *    whole meta step are fp32.  Requires d_0..d_{L-1} to be multiples of 8.
+ */
+#ifndef KAVG_H
+#define KAVG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KAVG_OK      0
+#define KAVG_EINVAL  1   /* bad argument                              */
+#define KAVG_ENOMEM  2   /* workspace too small                       */
+#define KAVG_EDEVICE 3   /* a HIP call failed                         */
+#define KAVG_ESTATE  4   /* call order misuse (e.g. no data set yet)  */
+
+#define KAVG_FP32 0
+#define KAVG_BF16 1
+
+typedef struct kavg_ctx kavg_ctx;
+
+/* n for an MLP with n_layers weight matrices; dims has n_layers+1 entries
+ * d_0..d_L.  Returns 0 on bad arguments. */
+size_t kavg_num_params(int n_layers, const int* dims);
+
+/* Bytes of device workspace kavg_init needs for this configuration (global
+ * model, momentum buffer, P replicas, bf16 shadows, index stream, activations,
+ * back-propagated gradients, losses).  Returns 0 on bad arguments. */
+size_t kavg_workspace_bytes(int P, int K, int B, int n_layers, const int* dims, int dtype);
+
+/* Create a context.  Hyper-parameters are those of Algorithm 1: P learners, K
+ * local steps per round, per-learner minibatch B, step size lr >= 0 (gamma_n =
+ * eta_n, fixed), block momentum mu in [0,1) (Theorem 1's range).
+ * index_seed seeds the minibatch index stream (see kavg_set_indices).
+ * workspace_dev: device block of at least kavg_workspace_bytes(...) bytes,
+ * 256-byte aligned, BORROWED until kavg_destroy.  hip_stream: a hipStream_t,
+ * BORROWED (NULL = default stream).
+ * Errors: KAVG_EINVAL (P,K,B < 1, P or the step count beyond 2^24, B > 65536,
+ * lr < 0, mu outside [0,1), n_layers < 1, a dim < 1, dims not multiples of 8
+ * with KAVG_BF16, unknown dtype, null pointers, misaligned workspace),
+ * KAVG_ENOMEM (workspace_bytes too small). */
+int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu,
+              int n_layers, const int* dims, int B, int dtype, uint64_t index_seed,
+              void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* "initialize w~_1; v <- 0" of Algorithm 1, and "set w^j = w~_1": copies n
+ * floats from w0_host into the global model, zeroes the momentum buffer,
+ * writes every replica (and bf16 shadow), resets round and step counters. */
+int kavg_set_params(kavg_ctx* ctx, const float* w0_host);
+
+/* Resume: global model w and momentum v (host, n floats each), round counter;
+ * replicas are rebroadcast from w; the local step counter becomes round*K. */
+int kavg_set_state(kavg_ctx* ctx, const float* w_host, const float* v_host, uint64_t round);
+
+/* The data set {(x_i, y_i)}: X_dev row-major [N][d_0], fp32 for KAVG_FP32 and
+ * bf16 (16-bit patterns) for KAVG_BF16; y_dev [N] class ids in [0, d_L).
+ * BORROWED.  N in [1, 2^31). */
+int kavg_set_data(kavg_ctx* ctx, const void* X_dev, const int32_t* y_dev, int64_t N);
+
+/* Minibatch sampling ("randomly sample a mini-batch of size B", Algorithm 1).
+ * idx_dev == NULL (default): learner j draws slot s of its t-th local step as
+ *   SplitMix64 output number (c+1) of a generator seeded with index_seed,
+ *   c = j*2^40 + t*2^16 + s, reduced mod N  -- i.i.d. uniform with replacement;
+ *   t counts the learner's local steps since kavg_set_params.
+ * idx_dev != NULL: int32 [P][K][B] device array used by every following
+ *   kavg_local_steps call (BORROWED; every entry must lie in [0, N), which is
+ *   checked on the device: offending entries are clamped into range and
+ *   kavg_local_steps's next synchronising call reports KAVG_EINVAL). */
+int kavg_set_indices(kavg_ctx* ctx, const int32_t* idx_dev);
+
+/* K local minibatch-SGD steps on each of the P learners (inner loop of
+ * Algorithm 1): sample, forward, softmax cross-entropy and its gradient,
+ * backward, in-place update of the learner's replica.  Asynchronous.
+ * Calling it twice without a meta update simply takes 2K local steps.
+ * Errors: KAVG_ESTATE without parameters or data, KAVG_EDEVICE. */
+int kavg_local_steps(kavg_ctx* ctx);
+
+/* The meta level of Algorithm 1 in one fused pass: average the replicas, block
+ * displacement d, block momentum v <- mu v + d, w~ <- w~ + v, and rebroadcast
+ * w~ to every replica (and shadow).  Asynchronous.  Increments the round. */
+int kavg_meta_update(kavg_ctx* ctx);
+
+/* Copy-outs (host pointers; each waits for the stream).  n must equal
+ * kavg_num_params, else KAVG_EINVAL. */
+int kavg_params(kavg_ctx* ctx, float* out_host, size_t n);            /* w~              */
+int kavg_momentum(kavg_ctx* ctx, float* out_host, size_t n);          /* v               */
+int kavg_replica(kavg_ctx* ctx, int j, float* out_host, size_t n);    /* w^j, 0 <= j < P */
+/* [K][P] mean minibatch loss of every learner at every step of the last kavg_local_steps */
+int kavg_losses(kavg_ctx* ctx, float* out_host);
+/* [P][K][B] indices used by the last kavg_local_steps */
+int kavg_indices(kavg_ctx* ctx, int32_t* out_host);
+
+uint64_t    kavg_round(const kavg_ctx* ctx);
+const char* kavg_last_error(const kavg_ctx* ctx);   /* ctx == NULL: text of the last failed kavg_init */
+int         kavg_destroy(kavg_ctx* ctx);            /* waits for the stream, frees the host context  */
+
+/* The fused meta step (same kernel as kavg_meta_update) on caller-owned
+ * arrays, for a flat parameter vector of any length n >= 1:
+ *   w_tilde_dev [n], v_dev [n]: updated in place;
+ *   replicas_dev: P replicas, replica j at replicas_dev + j*replica_stride
+ *     (replica_stride >= n, in floats); read, then overwritten with w~_{n+1};
+ *   shadow_dev: NULL, or bf16 copies written at shadow_dev + j*shadow_stride.
+ * Pointers 16-byte aligned and strides multiples of 4 (8 for the shadow) take
+ * the vector path; anything else takes a slower scalar path.  Asynchronous on
+ * hip_stream.  Errors: KAVG_EINVAL (P < 1, n < 1, stride < n, mu outside
+ * [0,1), null pointers), KAVG_EDEVICE. */
+int kavg_meta_update_flat(float* w_tilde_dev, float* v_dev, float* replicas_dev,
+                          size_t replica_stride, uint16_t* shadow_dev, size_t shadow_stride,
+                          int P, size_t n, float mu, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KAVG_H */

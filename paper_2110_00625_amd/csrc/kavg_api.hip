@@ -1,0 +1,381 @@
+// C boundary of the M-AVG hot path: context, workspace carve-up, and the
+// launch sequences of the learner loop and the meta step (Algorithm 1).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/kavg.h"
+#include "kavg_internal.h"
+
+using namespace kavg;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Layout {
+    size_t n = 0, stride = 0;          // parameters per replica, padded replica stride (elements)
+    int ldz = 0;                       // padded class count (logits / dZ_L leading dimension)
+    size_t off_w = 0, off_v = 0, off_reps = 0, off_shadow = 0, off_idx = 0, off_flag = 0;
+    size_t off_logits = 0, off_rowloss = 0, off_losses = 0;
+    std::vector<size_t> off_act, off_dz;   // per layer l = 1..L (index l-1); act of the last layer unused
+    std::vector<size_t> w_off, b_off;      // parameter offsets inside a replica
+    size_t total = 0;
+};
+
+bool shapes_ok(int P, int K, int B, int L, const int* dims, int dtype) {
+    if (P < 1 || K < 1 || B < 1 || L < 1 || !dims) return false;
+    if (P > (1 << 24) || K > (1 << 24) || B > (1 << 16)) return false;
+    if (dtype != KAVG_FP32 && dtype != KAVG_BF16) return false;
+    for (int l = 0; l <= L; ++l) {
+        if (dims[l] < 1 || dims[l] > (1 << 24)) return false;
+        if (dtype == KAVG_BF16 && l < L && dims[l] % 8 != 0) return false;
+    }
+    return true;
+}
+
+Layout make_layout(int P, int K, int B, int L, const int* dims, int dtype) {
+    Layout lo;
+    const size_t esz = dtype == KAVG_BF16 ? 2 : 4;     // activation / dZ element size
+    size_t o = 0;
+    for (int l = 1; l <= L; ++l) {
+        lo.w_off.push_back(o);
+        o += (size_t)dims[l] * dims[l - 1];
+        lo.b_off.push_back(o);
+        o += dims[l];
+    }
+    lo.n = o;
+    lo.stride = round_up(lo.n, 64);
+    lo.ldz = (int)round_up((size_t)dims[L], 8);
+    size_t p = 0;
+    auto take = [&](size_t bytes) { size_t at = p; p = round_up(p + bytes, ALIGN); return at; };
+    lo.off_w = take(lo.stride * 4);
+    lo.off_v = take(lo.stride * 4);
+    lo.off_reps = take((size_t)P * lo.stride * 4);
+    lo.off_shadow = dtype == KAVG_BF16 ? take((size_t)P * lo.stride * 2) : 0;
+    lo.off_idx = take((size_t)P * K * B * 4);
+    lo.off_flag = take(ALIGN);
+    for (int l = 1; l <= L; ++l) {
+        const size_t ld = l == L ? (size_t)lo.ldz : (size_t)dims[l];
+        lo.off_act.push_back(l < L ? take((size_t)P * B * ld * esz) : 0);
+        lo.off_dz.push_back(take((size_t)P * B * ld * esz));
+    }
+    lo.off_logits = take((size_t)P * B * lo.ldz * 4);
+    lo.off_rowloss = take((size_t)K * P * B * 4);
+    lo.off_losses = take((size_t)K * P * 4);
+    lo.total = p;
+    return lo;
+}
+
+char g_init_error[256] = "";
+
+}  // namespace
+
+struct kavg_ctx {
+    int P, K, B, L, dtype;
+    float lr, mu;
+    uint64_t seed;
+    std::vector<int> dims;
+    Layout lo;
+    char* ws;
+    hipStream_t stream;
+    const void* X;
+    const int32_t* y;
+    int64_t N;
+    const int32_t* user_idx;
+    uint32_t t0;          // local steps every learner has taken
+    uint64_t round;
+    bool have_params, have_steps;
+    char err[256];
+
+    float* w_tilde() const { return (float*)(ws + lo.off_w); }
+    float* v() const { return (float*)(ws + lo.off_v); }
+    float* reps() const { return (float*)(ws + lo.off_reps); }
+    uint16_t* shadow() const { return dtype == KAVG_BF16 ? (uint16_t*)(ws + lo.off_shadow) : nullptr; }
+    int32_t* idx() const { return (int32_t*)(ws + lo.off_idx); }
+    int* flag() const { return (int*)(ws + lo.off_flag); }
+    float* logits() const { return (float*)(ws + lo.off_logits); }
+    float* rowloss() const { return (float*)(ws + lo.off_rowloss); }
+    float* losses() const { return (float*)(ws + lo.off_losses); }
+};
+
+namespace {
+
+int fail(kavg_ctx* c, int code, const char* fmt, ...) {
+    char* dst = c ? c->err : g_init_error;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, 256, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define KAVG_HIP(ctx, call)                                                                   \
+    do {                                                                                      \
+        hipError_t e_ = (call);                                                               \
+        if (e_ != hipSuccess) return fail(ctx, KAVG_EDEVICE, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+// wait for the stream, then report (and clear) the device-side range flag
+int sync_and_check(kavg_ctx* c) {
+    int flag = 0;
+    KAVG_HIP(c, hipMemcpyAsync(&flag, c->flag(), sizeof(int), hipMemcpyDeviceToHost, c->stream));
+    KAVG_HIP(c, hipStreamSynchronize(c->stream));
+    if (flag) {
+        KAVG_HIP(c, hipMemsetAsync(c->flag(), 0, sizeof(int), c->stream));
+        KAVG_HIP(c, hipStreamSynchronize(c->stream));
+        return fail(c, KAVG_EINVAL, "an index or label outside its range was found on the device");
+    }
+    return KAVG_OK;
+}
+
+int install_global(kavg_ctx* c, const float* w_host, const float* v_host) {
+    KAVG_HIP(c, hipMemcpyAsync(c->w_tilde(), w_host, c->lo.n * 4, hipMemcpyHostToDevice, c->stream));
+    if (v_host)
+        KAVG_HIP(c, hipMemcpyAsync(c->v(), v_host, c->lo.n * 4, hipMemcpyHostToDevice, c->stream));
+    else
+        KAVG_HIP(c, hipMemsetAsync(c->v(), 0, c->lo.stride * 4, c->stream));
+    KAVG_HIP(c, launch_broadcast(c->w_tilde(), c->reps(), c->lo.stride, c->shadow(), c->lo.stride, c->P,
+                                 c->lo.n, c->stream));
+    KAVG_HIP(c, hipStreamSynchronize(c->stream));   // host buffers may be reused by the caller
+    c->have_params = true;
+    c->have_steps = false;
+    return KAVG_OK;
+}
+
+LayerCall layer_call(const kavg_ctx* c, int l /*1..L*/, int k) {
+    const Layout& lo = c->lo;
+    const size_t esz = c->dtype == KAVG_BF16 ? 2 : 4;
+    const int L = c->L;
+    LayerCall q = {};
+    q.P = c->P; q.B = c->B;
+    q.d_in = c->dims[l - 1]; q.d_out = c->dims[l];
+    q.w = c->reps() + lo.w_off[l - 1]; q.w_stride = lo.stride;
+    q.b = c->reps() + lo.b_off[l - 1];
+    q.ws = c->shadow() ? c->shadow() + lo.w_off[l - 1] : nullptr; q.ws_stride = lo.stride;
+    if (l == 1) {
+        q.in = c->X; q.ld_in = c->dims[0]; q.in_stride = 0;
+        q.gather = c->idx() + (size_t)k * c->B; q.gather_stride = (long)c->K * c->B;
+    } else {
+        q.in = c->ws + lo.off_act[l - 2]; q.ld_in = c->dims[l - 1]; q.in_stride = (size_t)c->B * q.ld_in;
+        q.dz_prev = c->ws + lo.off_dz[l - 2]; q.dz_prev_stride = (size_t)c->B * q.ld_in;
+    }
+    if (l < L) {
+        q.out = c->ws + lo.off_act[l - 1]; q.ld_out = c->dims[l]; q.relu = 1;
+    } else {
+        q.out = c->logits(); q.ld_out = lo.ldz; q.relu = 0;
+    }
+    q.out_stride = (size_t)c->B * q.ld_out;
+    q.dz = c->ws + lo.off_dz[l - 1]; q.ld_dz = l == L ? lo.ldz : c->dims[l];
+    q.dz_stride = (size_t)c->B * q.ld_dz;
+    q.lr = c->lr;
+    (void)esz;
+    return q;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t kavg_num_params(int n_layers, const int* dims) {
+    if (n_layers < 1 || !dims) return 0;
+    size_t n = 0;
+    for (int l = 1; l <= n_layers; ++l) {
+        if (dims[l] < 1 || dims[l - 1] < 1) return 0;
+        n += (size_t)dims[l] * dims[l - 1] + dims[l];
+    }
+    return n;
+}
+
+size_t kavg_workspace_bytes(int P, int K, int B, int n_layers, const int* dims, int dtype) {
+    if (!shapes_ok(P, K, B, n_layers, dims, dtype)) return 0;
+    return make_layout(P, K, B, n_layers, dims, dtype).total;
+}
+
+int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, const int* dims, int B,
+              int dtype, uint64_t index_seed, void* workspace_dev, size_t workspace_bytes,
+              void* hip_stream) {
+    if (!out) return fail(nullptr, KAVG_EINVAL, "out is null");
+    *out = nullptr;
+    if (!shapes_ok(P, K, B, n_layers, dims, dtype))
+        return fail(nullptr, KAVG_EINVAL, "bad shape: need P,K,B >= 1 (P,K <= 2^24, B <= 65536), "
+                    "dims >= 1 and, for bf16, d_0..d_{L-1} multiples of 8");
+    if (!(lr >= 0.f) || !std::isfinite(lr)) return fail(nullptr, KAVG_EINVAL, "lr must be finite and >= 0");
+    if (!(mu >= 0.f && mu < 1.f)) return fail(nullptr, KAVG_EINVAL, "mu must lie in [0,1)");
+    if (!workspace_dev || ((uintptr_t)workspace_dev % ALIGN) != 0)
+        return fail(nullptr, KAVG_EINVAL, "workspace must be a non-null, 256-byte aligned device pointer");
+    Layout lo = make_layout(P, K, B, n_layers, dims, dtype);
+    if (workspace_bytes < lo.total)
+        return fail(nullptr, KAVG_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, lo.total);
+    kavg_ctx* c = new (std::nothrow) kavg_ctx();
+    if (!c) return fail(nullptr, KAVG_ENOMEM, "host allocation failed");
+    c->P = P; c->K = K; c->B = B; c->L = n_layers; c->dtype = dtype;
+    c->lr = lr; c->mu = mu; c->seed = index_seed;
+    c->dims.assign(dims, dims + n_layers + 1);
+    c->lo = lo;
+    c->ws = (char*)workspace_dev;
+    c->stream = (hipStream_t)hip_stream;
+    c->X = nullptr; c->y = nullptr; c->N = 0; c->user_idx = nullptr;
+    c->t0 = 0; c->round = 0; c->have_params = false; c->have_steps = false;
+    c->err[0] = 0;
+    hipError_t e = hipMemsetAsync(c->flag(), 0, ALIGN, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) {
+        fail(nullptr, KAVG_EDEVICE, "clearing the workspace flag failed: %s", hipGetErrorString(e));
+        delete c;
+        return KAVG_EDEVICE;
+    }
+    *out = c;
+    return KAVG_OK;
+}
+
+int kavg_set_params(kavg_ctx* c, const float* w0_host) {
+    if (!c) return KAVG_EINVAL;
+    if (!w0_host) return fail(c, KAVG_EINVAL, "w0_host is null");
+    c->t0 = 0;
+    c->round = 0;
+    return install_global(c, w0_host, nullptr);
+}
+
+int kavg_set_state(kavg_ctx* c, const float* w_host, const float* v_host, uint64_t round) {
+    if (!c) return KAVG_EINVAL;
+    if (!w_host || !v_host) return fail(c, KAVG_EINVAL, "null state pointer");
+    if (round > ((uint64_t)1 << 24) / (uint64_t)c->K) return fail(c, KAVG_EINVAL, "round*K exceeds 2^24 local steps");
+    c->round = round;
+    c->t0 = (uint32_t)(round * (uint64_t)c->K);
+    return install_global(c, w_host, v_host);
+}
+
+int kavg_set_data(kavg_ctx* c, const void* X_dev, const int32_t* y_dev, int64_t N) {
+    if (!c) return KAVG_EINVAL;
+    if (!X_dev || !y_dev) return fail(c, KAVG_EINVAL, "null data pointer");
+    if (N < 1 || N >= ((int64_t)1 << 31)) return fail(c, KAVG_EINVAL, "N must lie in [1, 2^31)");
+    if (((uintptr_t)X_dev & 15) != 0) return fail(c, KAVG_EINVAL, "X_dev must be 16-byte aligned");
+    KAVG_HIP(c, launch_label_check(y_dev, (size_t)N, c->dims[c->L], c->flag(), c->stream));
+    int rc = sync_and_check(c);
+    if (rc != KAVG_OK) return rc == KAVG_EINVAL ? fail(c, KAVG_EINVAL, "a label lies outside [0, d_L)") : rc;
+    c->X = X_dev; c->y = y_dev; c->N = N;
+    return KAVG_OK;
+}
+
+int kavg_set_indices(kavg_ctx* c, const int32_t* idx_dev) {
+    if (!c) return KAVG_EINVAL;
+    c->user_idx = idx_dev;
+    return KAVG_OK;
+}
+
+int kavg_local_steps(kavg_ctx* c) {
+    if (!c) return KAVG_EINVAL;
+    if (!c->have_params) return fail(c, KAVG_ESTATE, "no parameters: call kavg_set_params first");
+    if (!c->X) return fail(c, KAVG_ESTATE, "no data set: call kavg_set_data first");
+    if ((uint64_t)c->t0 + (uint64_t)c->K > ((uint64_t)1 << 24))
+        return fail(c, KAVG_ESTATE, "local step counter would exceed 2^24");
+    hipStream_t st = c->stream;
+    const bool bf = c->dtype == KAVG_BF16;
+    const int L = c->L;
+    if (c->user_idx)
+        KAVG_HIP(c, launch_index_import(c->idx(), c->user_idx, (size_t)c->P * c->K * c->B, (uint32_t)c->N,
+                                        c->flag(), st));
+    else
+        KAVG_HIP(c, launch_index_stream(c->idx(), c->P, c->K, c->B, c->seed, c->t0, (uint32_t)c->N, st));
+
+    for (int k = 0; k < c->K; ++k) {
+        for (int l = 1; l <= L; ++l) {                       // forward
+            LayerCall q = layer_call(c, l, k);
+            KAVG_HIP(c, bf ? bf16_forward(q, st) : f32_forward(q, st));
+        }
+        KAVG_HIP(c, launch_softmax_ce(c->logits(), c->lo.ldz, c->dims[L], c->y, c->idx() + (size_t)k * c->B,
+                                      (long)c->K * c->B, c->B, c->P, c->ws + c->lo.off_dz[L - 1], bf ? 1 : 0,
+                                      c->rowloss() + (size_t)k * c->P * c->B, st));
+        for (int l = L; l >= 1; --l) {                       // backward; W_l is read before it is updated
+            LayerCall q = layer_call(c, l, k);
+            if (l > 1) KAVG_HIP(c, bf ? bf16_backward_data(q, st) : f32_backward_data(q, st));
+            KAVG_HIP(c, bf ? bf16_update(q, st) : f32_update(q, st));
+        }
+    }
+    KAVG_HIP(c, launch_loss_mean(c->rowloss(), c->losses(), c->K * c->P, c->B, st));
+    c->t0 += (uint32_t)c->K;
+    c->have_steps = true;
+    return KAVG_OK;
+}
+
+int kavg_meta_update(kavg_ctx* c) {
+    if (!c) return KAVG_EINVAL;
+    if (!c->have_params) return fail(c, KAVG_ESTATE, "no parameters: call kavg_set_params first");
+    KAVG_HIP(c, launch_meta_update(c->w_tilde(), c->v(), c->reps(), c->lo.stride, c->shadow(), c->lo.stride,
+                                   c->P, c->lo.n, c->mu, c->stream));
+    c->round += 1;
+    return KAVG_OK;
+}
+
+static int copy_out(kavg_ctx* c, const void* src, void* dst_host, size_t bytes) {
+    KAVG_HIP(c, hipMemcpyAsync(dst_host, src, bytes, hipMemcpyDeviceToHost, c->stream));
+    return sync_and_check(c);
+}
+
+int kavg_params(kavg_ctx* c, float* out_host, size_t n) {
+    if (!c) return KAVG_EINVAL;
+    if (!out_host || n != c->lo.n) return fail(c, KAVG_EINVAL, "need a buffer of exactly %zu floats", c->lo.n);
+    if (!c->have_params) return fail(c, KAVG_ESTATE, "no parameters yet");
+    return copy_out(c, c->w_tilde(), out_host, n * 4);
+}
+
+int kavg_momentum(kavg_ctx* c, float* out_host, size_t n) {
+    if (!c) return KAVG_EINVAL;
+    if (!out_host || n != c->lo.n) return fail(c, KAVG_EINVAL, "need a buffer of exactly %zu floats", c->lo.n);
+    if (!c->have_params) return fail(c, KAVG_ESTATE, "no parameters yet");
+    return copy_out(c, c->v(), out_host, n * 4);
+}
+
+int kavg_replica(kavg_ctx* c, int j, float* out_host, size_t n) {
+    if (!c) return KAVG_EINVAL;
+    if (!out_host || n != c->lo.n) return fail(c, KAVG_EINVAL, "need a buffer of exactly %zu floats", c->lo.n);
+    if (j < 0 || j >= c->P) return fail(c, KAVG_EINVAL, "learner %d outside [0,%d)", j, c->P);
+    if (!c->have_params) return fail(c, KAVG_ESTATE, "no parameters yet");
+    return copy_out(c, c->reps() + (size_t)j * c->lo.stride, out_host, n * 4);
+}
+
+int kavg_losses(kavg_ctx* c, float* out_host) {
+    if (!c) return KAVG_EINVAL;
+    if (!out_host) return fail(c, KAVG_EINVAL, "out_host is null");
+    if (!c->have_steps) return fail(c, KAVG_ESTATE, "no local steps taken yet");
+    return copy_out(c, c->losses(), out_host, (size_t)c->K * c->P * 4);
+}
+
+int kavg_indices(kavg_ctx* c, int32_t* out_host) {
+    if (!c) return KAVG_EINVAL;
+    if (!out_host) return fail(c, KAVG_EINVAL, "out_host is null");
+    if (!c->have_steps) return fail(c, KAVG_ESTATE, "no local steps taken yet");
+    return copy_out(c, c->idx(), out_host, (size_t)c->P * c->K * c->B * 4);
+}
+
+uint64_t kavg_round(const kavg_ctx* c) { return c ? c->round : 0; }
+
+const char* kavg_last_error(const kavg_ctx* c) { return c ? c->err : g_init_error; }
+
+int kavg_destroy(kavg_ctx* c) {
+    if (!c) return KAVG_EINVAL;
+    hipError_t e = hipStreamSynchronize(c->stream);
+    delete c;
+    return e == hipSuccess ? KAVG_OK : KAVG_EDEVICE;
+}
+
+int kavg_meta_update_flat(float* w_tilde_dev, float* v_dev, float* replicas_dev, size_t replica_stride,
+                          uint16_t* shadow_dev, size_t shadow_stride, int P, size_t n, float mu,
+                          void* hip_stream) {
+    if (!w_tilde_dev || !v_dev || !replicas_dev) return KAVG_EINVAL;
+    if (P < 1 || n < 1 || replica_stride < n || !(mu >= 0.f && mu < 1.f)) return KAVG_EINVAL;
+    if (shadow_dev && shadow_stride < n) return KAVG_EINVAL;
+    hipError_t e = launch_meta_update(w_tilde_dev, v_dev, replicas_dev, replica_stride, shadow_dev,
+                                      shadow_stride, P, n, mu, (hipStream_t)hip_stream);
+    return e == hipSuccess ? KAVG_OK : KAVG_EDEVICE;
+}
+
+}  // extern "C"

@@ -1,0 +1,68 @@
+// Internal launch interface between the C boundary (kavg_api.hip) and the
+// kernel translation units.  Every launcher validates nothing: the boundary
+// has already checked shapes; launchers only derive grids from them.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace kavg {
+
+// ---- minibatch index stream (Algorithm 1: "randomly sample a mini-batch") ----
+// idx[P][K][B], entry (j,k,s) = SplitMix64 draw with counter j*2^40 + (t0+k)*2^16 + s, mod N.
+hipError_t launch_index_stream(int32_t* idx, int P, int K, int B, uint64_t seed,
+                               uint32_t t0, uint32_t N, hipStream_t st);
+// copy caller indices into idx, clamping into [0,N) and raising *flag on any entry outside
+hipError_t launch_index_import(int32_t* idx, const int32_t* user, size_t count, uint32_t N,
+                               int* flag, hipStream_t st);
+// raise *flag if any label lies outside [0,C)
+hipError_t launch_label_check(const int32_t* y, size_t N, int C, int* flag, hipStream_t st);
+
+// ---- meta level (Algorithm 1: a, d, v, w~, restart of the learners) ----
+hipError_t launch_meta_update(float* w_tilde, float* v, float* reps, size_t stride,
+                              uint16_t* shadow, size_t sstride, int P, size_t n, float mu,
+                              hipStream_t st);
+// w^j <- w~ for all j (and shadows): the "set w^j = w~_n" of the first round
+hipError_t launch_broadcast(const float* w_tilde, float* reps, size_t stride,
+                            uint16_t* shadow, size_t sstride, int P, size_t n, hipStream_t st);
+
+// ---- loss and its gradient ----
+// logits [P][B][ldz] fp32; labels y[idx[j][m]]; dz [P][B][ldz] (fp32 or bf16), pad columns zeroed;
+// rowloss [P][B].  dZ = (softmax - onehot)/B.
+hipError_t launch_softmax_ce(const float* logits, int ldz, int C, const int32_t* y,
+                             const int32_t* idx, long idx_learner_stride, int B, int P,
+                             void* dz, int dz_bf16, float* rowloss, hipStream_t st);
+// losses[k][j] = mean_m rowloss[k][j][m]
+hipError_t launch_loss_mean(const float* rowloss, float* losses, int KP, int B, hipStream_t st);
+
+// ---- per-learner dense layers ----
+struct LayerCall {
+    int P, B;              // learners, rows per learner
+    int d_in, d_out;       // layer shape: W [d_out][d_in]
+    // parameters: learner j's W at w + j*w_stride (fp32 master) / ws + j*ws_stride (bf16 shadow)
+    float* w;       size_t w_stride;      // master weights of this layer (first learner)
+    float* b;                               // master bias of this layer (same stride)
+    uint16_t* ws;   size_t ws_stride;     // bf16 shadow of w (bf16 mode), else null
+    // activations entering the layer: [P][B][ld_in]; or, with gather != null, rows X[gather[j][m]]
+    const void* in; int ld_in; size_t in_stride;
+    const int32_t* gather; long gather_stride;
+    // activations leaving the layer / logits: [P][B][ld_out]
+    void* out; int ld_out; size_t out_stride;
+    // gradient w.r.t. this layer's pre-activation: [P][B][ld_dz]
+    const void* dz; int ld_dz; size_t dz_stride;
+    // gradient w.r.t. the previous layer's pre-activation (output of backward-data): [P][B][ld_in]
+    void* dz_prev; size_t dz_prev_stride;
+    int relu;              // forward: apply ReLU (hidden layer) / keep fp32 logits (last layer)
+    float lr;
+};
+
+// fp32 path
+hipError_t f32_forward(const LayerCall& c, hipStream_t st);
+hipError_t f32_backward_data(const LayerCall& c, hipStream_t st);
+hipError_t f32_update(const LayerCall& c, hipStream_t st);
+// bf16 MFMA path
+hipError_t bf16_forward(const LayerCall& c, hipStream_t st);
+hipError_t bf16_backward_data(const LayerCall& c, hipStream_t st);
+hipError_t bf16_update(const LayerCall& c, hipStream_t st);
+
+}  // namespace kavg

@@ -1,0 +1,217 @@
+"""ctypes binding of libkavg.so: the same calls as include/kavg.h, argument
+marshalling only.  PyTorch supplies device memory and the stream; every step
+of the method runs inside the library's HIP kernels.  There is no fallback:
+if the library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkavg.so")
+
+KAVG_OK, KAVG_EINVAL, KAVG_ENOMEM, KAVG_EDEVICE, KAVG_ESTATE = 0, 1, 2, 3, 4
+KAVG_FP32, KAVG_BF16 = 0, 1
+_CODES = {1: "KAVG_EINVAL", 2: "KAVG_ENOMEM", 3: "KAVG_EDEVICE", 4: "KAVG_ESTATE"}
+
+EXPORTS = [
+    "kavg_num_params", "kavg_workspace_bytes", "kavg_init", "kavg_set_params", "kavg_set_state",
+    "kavg_set_data", "kavg_set_indices", "kavg_local_steps", "kavg_meta_update", "kavg_params",
+    "kavg_momentum", "kavg_replica", "kavg_losses", "kavg_indices", "kavg_round", "kavg_last_error",
+    "kavg_destroy", "kavg_meta_update_flat",
+]
+
+
+class KavgError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("%s: %s" % (_CODES.get(code, code), text))
+        self.code = code
+
+
+_lib = None
+
+
+def load_library():
+    """Load libkavg.so built in-tree; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            "%s not found: build it with `python -m paper_2110_00625_amd.build`" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    c_int, c_f, c_sz, c_vp = ctypes.c_int, ctypes.c_float, ctypes.c_size_t, ctypes.c_void_p
+    ip = ctypes.POINTER(ctypes.c_int)
+    lib.kavg_num_params.restype = c_sz
+    lib.kavg_num_params.argtypes = [c_int, ip]
+    lib.kavg_workspace_bytes.restype = c_sz
+    lib.kavg_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, ip, c_int]
+    lib.kavg_init.restype = c_int
+    lib.kavg_init.argtypes = [ctypes.POINTER(c_vp), c_int, c_int, c_f, c_f, c_int, ip, c_int, c_int,
+                              ctypes.c_uint64, c_vp, c_sz, c_vp]
+    for name, args in {
+        "kavg_set_params": [c_vp, c_vp],
+        "kavg_set_state": [c_vp, c_vp, c_vp, ctypes.c_uint64],
+        "kavg_set_data": [c_vp, c_vp, c_vp, ctypes.c_int64],
+        "kavg_set_indices": [c_vp, c_vp],
+        "kavg_local_steps": [c_vp],
+        "kavg_meta_update": [c_vp],
+        "kavg_params": [c_vp, c_vp, c_sz],
+        "kavg_momentum": [c_vp, c_vp, c_sz],
+        "kavg_replica": [c_vp, c_int, c_vp, c_sz],
+        "kavg_losses": [c_vp, c_vp],
+        "kavg_indices": [c_vp, c_vp],
+        "kavg_destroy": [c_vp],
+        "kavg_meta_update_flat": [c_vp, c_vp, c_vp, c_sz, c_vp, c_sz, c_int, c_sz, c_f, c_vp],
+    }.items():
+        fn = getattr(lib, name)
+        fn.restype = c_int
+        fn.argtypes = args
+    lib.kavg_round.restype = ctypes.c_uint64
+    lib.kavg_round.argtypes = [c_vp]
+    lib.kavg_last_error.restype = ctypes.c_char_p
+    lib.kavg_last_error.argtypes = [c_vp]
+    _lib = lib
+    return lib
+
+
+def _dims_array(dims):
+    return (ctypes.c_int * len(dims))(*[int(d) for d in dims])
+
+
+def _check(lib, ctx, rc):
+    if rc != KAVG_OK:
+        raise KavgError(rc, lib.kavg_last_error(ctx).decode())
+
+
+def kavg_num_params(dims):
+    return int(load_library().kavg_num_params(len(dims) - 1, _dims_array(dims)))
+
+
+def kavg_workspace_bytes(P, K, B, dims, dtype):
+    return int(load_library().kavg_workspace_bytes(P, K, B, len(dims) - 1, _dims_array(dims), dtype))
+
+
+def kavg_meta_update_flat(w_tilde, v, replicas, mu, shadow=None, stream=None):
+    """Fused meta step on caller tensors: w_tilde [n], v [n], replicas [P][stride>=n] (fp32,
+    device); shadow None or int16/bfloat16 [P][sstride]."""
+    import torch
+    lib = load_library()
+    P, n = replicas.shape[0], w_tilde.numel()
+    st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    rc = lib.kavg_meta_update_flat(w_tilde.data_ptr(), v.data_ptr(), replicas.data_ptr(),
+                                   replicas.stride(0), None if shadow is None else shadow.data_ptr(),
+                                   0 if shadow is None else shadow.stride(0), P, n, float(mu), st)
+    if rc != KAVG_OK:
+        raise KavgError(rc, "kavg_meta_update_flat rejected its arguments" if rc == KAVG_EINVAL
+                        else "HIP launch failed")
+
+
+class MAvg:
+    """One kavg_ctx plus the torch tensors it borrows (workspace, data set, indices)."""
+
+    def __init__(self, P, K, lr, mu, dims, B, dtype=KAVG_FP32, index_seed=0, device="cuda:0"):
+        import torch
+        self._torch = torch
+        self.lib = load_library()
+        self.P, self.K, self.B, self.dims, self.dtype = P, K, B, tuple(int(d) for d in dims), dtype
+        self.device = torch.device(device)
+        self.ctx = ctypes.c_void_p()
+        nbytes = kavg_workspace_bytes(P, K, B, self.dims, dtype)
+        if nbytes == 0:
+            raise KavgError(KAVG_EINVAL, "kavg_workspace_bytes rejected the configuration")
+        torch.cuda.set_device(self.device)
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.stream = torch.cuda.current_stream(self.device)
+        rc = self.lib.kavg_init(ctypes.byref(self.ctx), P, K, float(lr), float(mu), len(self.dims) - 1,
+                                _dims_array(self.dims), B, dtype, int(index_seed),
+                                self.workspace.data_ptr(), nbytes, self.stream.cuda_stream)
+        if rc != KAVG_OK:
+            raise KavgError(rc, self.lib.kavg_last_error(None).decode())
+        self.n = kavg_num_params(self.dims)
+        self._keep = {}
+
+    # -- inputs -----------------------------------------------------------
+    def set_params(self, w0):
+        w0 = np.ascontiguousarray(w0, dtype=np.float32)
+        assert w0.size == self.n
+        _check(self.lib, self.ctx, self.lib.kavg_set_params(self.ctx, w0.ctypes.data))
+
+    def set_state(self, w, v, round_):
+        w = np.ascontiguousarray(w, dtype=np.float32)
+        v = np.ascontiguousarray(v, dtype=np.float32)
+        assert w.size == self.n and v.size == self.n
+        _check(self.lib, self.ctx, self.lib.kavg_set_state(self.ctx, w.ctypes.data, v.ctypes.data, int(round_)))
+
+    def set_data(self, X_dev, y_dev):
+        """X_dev: device tensor [N][d0], float32 (fp32 mode) or bfloat16/int16 bit patterns (bf16 mode);
+        y_dev: device int32 [N]."""
+        torch = self._torch
+        assert X_dev.is_cuda and y_dev.is_cuda and X_dev.is_contiguous() and y_dev.is_contiguous()
+        assert y_dev.dtype == torch.int32 and X_dev.shape[1] == self.dims[0]
+        if self.dtype == KAVG_FP32:
+            assert X_dev.dtype == torch.float32
+        else:
+            assert X_dev.dtype in (torch.bfloat16, torch.int16, torch.uint16)
+        self._keep["X"], self._keep["y"] = X_dev, y_dev
+        _check(self.lib, self.ctx, self.lib.kavg_set_data(self.ctx, X_dev.data_ptr(), y_dev.data_ptr(),
+                                                          X_dev.shape[0]))
+
+    def set_indices(self, idx_dev):
+        if idx_dev is None:
+            self._keep.pop("idx", None)
+            _check(self.lib, self.ctx, self.lib.kavg_set_indices(self.ctx, None))
+            return
+        assert idx_dev.is_cuda and idx_dev.dtype == self._torch.int32 and idx_dev.is_contiguous()
+        assert idx_dev.numel() == self.P * self.K * self.B
+        self._keep["idx"] = idx_dev
+        _check(self.lib, self.ctx, self.lib.kavg_set_indices(self.ctx, idx_dev.data_ptr()))
+
+    # -- the hot path -------------------------------------------------------
+    def local_steps(self):
+        _check(self.lib, self.ctx, self.lib.kavg_local_steps(self.ctx))
+
+    def meta_update(self):
+        _check(self.lib, self.ctx, self.lib.kavg_meta_update(self.ctx))
+
+    # -- outputs ----------------------------------------------------------
+    def _out(self, fn, *pre):
+        out = np.empty(self.n, dtype=np.float32)
+        _check(self.lib, self.ctx, fn(self.ctx, *pre, out.ctypes.data, self.n))
+        return out
+
+    def params(self):
+        return self._out(self.lib.kavg_params)
+
+    def momentum(self):
+        return self._out(self.lib.kavg_momentum)
+
+    def replica(self, j):
+        return self._out(self.lib.kavg_replica, int(j))
+
+    def losses(self):
+        out = np.empty((self.K, self.P), dtype=np.float32)
+        _check(self.lib, self.ctx, self.lib.kavg_losses(self.ctx, out.ctypes.data))
+        return out
+
+    def indices(self):
+        out = np.empty((self.P, self.K, self.B), dtype=np.int32)
+        _check(self.lib, self.ctx, self.lib.kavg_indices(self.ctx, out.ctypes.data))
+        return out
+
+    def round(self):
+        return int(self.lib.kavg_round(self.ctx))
+
+    def close(self):
+        if self.ctx:
+            self.lib.kavg_destroy(self.ctx)
+            self.ctx = ctypes.c_void_p()
+            self._keep.clear()
+            self.workspace = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
