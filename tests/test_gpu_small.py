@@ -148,6 +148,32 @@ def test_fp32_learner_loop_and_meta_step(P, K, B, dims):
     g.close()
 
 
+# ----------------------------------------------------------------- learner loop, bf16 operands
+@pytest.mark.parametrize("P,K,B,dims", [
+    (3, 3, 40, (264, 200, 136, 10)),      # ragged tiles in every dimension, B below one row tile
+    (2, 2, 150, (136, 328, 150)),          # B spans two row tiles, class count spans two tiles
+    (2, 2, 64, (72, 264, 8, 10)),          # the 64-row tile, a hidden layer narrower than any tile
+    (2, 2, 9, (40, 3)),                    # single layer
+])
+def test_bf16_learner_loop_and_meta_step(P, K, B, dims):
+    g, o = _pair(P, K, 0.05, 0.9, dims, B, True, seed=51)
+    _run_and_compare(g, o, dims, rounds=3, tol=TOL_BF16, tag="bf16 %s" % (dims,))
+    g.close()
+
+
+def test_bf16_one_step_is_tight():
+    """A single local step from identical state: only accumulation order and the fp32
+    master rounding separate the two sides, far below the free-running tolerance."""
+    dims = (264, 200, 136, 10)
+    g, o = _pair(2, 1, 0.05, 0.0, dims, 40, True, seed=61)
+    g.local_steps()
+    o.local_steps()
+    for j in range(2):
+        e = worst_error(g.replica(j), o.replica(j), dims)
+        assert e < 2e-4, e
+    g.close()
+
+
 def test_lr0_is_bit_exact_on_the_gpu():
     dims = (64, 48, 10)
     g, o = _pair(3, 2, 0.0, 0.9, dims, 16, False, seed=21)
