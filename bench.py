@@ -1,0 +1,250 @@
+#!/usr/bin/env python3
+"""Benchmark of the M-AVG hot path on one MI355X.
+
+A "step" is one meta round of Algorithm 1 on synthetic data: K local
+minibatch-SGD steps on each of the P learners (kavg_local_steps) followed by
+the fused meta step (kavg_meta_update).  Prints ONE JSON line:
+
+  value       learner-samples/s = P*K*B*steps / wall time of the timed rounds
+              (inputs resident in device memory before the clock starts)
+  roofline    the dominant kernel class of the round, its algorithmic bytes
+              per launch over its average launch duration (HIP events on the
+              library's stream, recorded inside the timed region)
+  cpu_baseline  the CPU oracle, as it stands, on a bounded sample of the same
+              workload (reported for context, not a target)
+  meta_update the fused meta step alone on the meta-only workload
+              (P=64 replicas of an 11.2M-parameter fp32 vector), GB/s vs HBM peak
+"""
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2110_00625_amd import kavg, synth                                   # noqa: E402
+from paper_2110_00625_amd.configs import (WORKLOADS, META_ONLY, flops_per_learner_step,  # noqa: E402
+                                          num_params)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
+FP32_PEAK_TFLOPS = 157.3
+
+
+def class_model(w):
+    """Algorithmic bytes and flops of one launch-set (all layers) of each kernel
+    class for ONE local step of all P learners, and of one meta pass."""
+    P, B, d = w.P, w.B, w.dims
+    L = len(d) - 1
+    bf = w.dtype == kavg.KAVG_BF16
+    e = 2 if bf else 4                      # operand element size
+    ldz = (d[L] + 7) // 8 * 8
+    by = {"forward": 0, "backward": 0, "update": 0}
+    fl = {"forward": 0, "backward": 0, "update": 0}
+    for l in range(1, L + 1):
+        wsz = d[l] * d[l - 1]
+        ld_out = ldz if l == L else d[l]
+        # forward: weights once, bias, input rows, output rows
+        by["forward"] += P * (e * wsz + 4 * d[l] + e * B * d[l - 1] + (4 * B * ld_out if l == L else e * B * d[l]))
+        fl["forward"] += P * 2 * B * wsz
+        # update: master read + write (+ shadow write), bias read + write, dZ and A once
+        by["update"] += P * ((8 + (2 if bf else 0)) * wsz + 8 * d[l] + e * B * (ld_out + d[l - 1]))
+        fl["update"] += P * 2 * B * wsz
+        if l > 1:   # data gradient: weights once, dZ_l, mask read, dZ_{l-1} written
+            by["backward"] += P * (e * wsz + e * B * ld_out + 2 * e * B * d[l - 1])
+            fl["backward"] += P * 2 * B * wsz
+    n = num_params(d)
+    by["meta"] = (2 * P + 4) * 4 * n + (2 * P * n if bf else 0)
+    fl["meta"] = (2 * P + 3) * n
+    return by, fl
+
+
+def source_digest():
+    h = hashlib.sha256()
+    for f in sorted(os.listdir(os.path.join(ROOT, "paper_2110_00625_amd", "csrc"))):
+        with open(os.path.join(ROOT, "paper_2110_00625_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def stored_traffic(kernel_class):
+    """HBM bytes per launch from the rocprofv3 --pmc runs recorded under profiles/,
+    or None when absent or taken from other kernel sources than the current ones."""
+    path = os.path.join(ROOT, "profiles", "pmc_traffic.json.txt")
+    if not os.path.exists(path):
+        return None
+    try:
+        rec = json.load(open(path))
+    except Exception:
+        return None
+    if rec.get("source_digest") != source_digest():
+        return None
+    return rec.get("traffic_bytes_per_launch", {}).get(kernel_class)
+
+
+def cpu_baseline(w, data, learners):
+    """The oracle on `learners` learners x K steps of this workload."""
+    from threadpoolctl import threadpool_info
+    from oracle import mavg_oracle as O
+    o = O.MAvgOracle(w.P, w.K, w.lr, w.mu, w.dims, w.B, bf16=(w.dtype == kavg.KAVG_BF16),
+                     index_seed=w.seeds["index"])
+    o.set_data(data["X32"], data["y"])
+    o.set_params(data["w0"])
+    t0 = time.perf_counter()
+    o.local_steps(learners=list(range(learners)))
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+    return {"value": learners * w.K * w.B / dt, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d of %d learners x K=%d local steps of the same workload (%.1f s)" % (
+                learners, w.P, w.K, dt)}
+
+
+def bench_meta_only(torch, passes=200, warmup=5):
+    w = META_ONLY
+    n, P = w.flat_n, w.P
+    stride = (n + 63) // 64 * 64
+    g = torch.Generator(device="cuda").manual_seed(w.seeds["data"])
+    base = torch.randn(n, device="cuda", generator=g) * 0.05
+    v = torch.randn(n, device="cuda", generator=g) * 1e-3
+    reps = torch.empty((P, stride), device="cuda")
+    reps[:, :n] = base + torch.randn((P, n), device="cuda", generator=g) * 1e-3
+    wt = base.clone()
+    for _ in range(warmup):
+        kavg.kavg_meta_update_flat(wt, v, reps, w.mu)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(passes):
+        kavg.kavg_meta_update_flat(wt, v, reps, w.mu)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / passes
+    bytes_pass = (2 * P + 4) * 4 * n
+    gbs = bytes_pass / (ms * 1e-3) / 1e9
+    return {"workload": "meta_only: P=%d replicas of n=%d fp32, mu=%.2f, %d passes" % (P, n, w.mu, passes),
+            "ms_per_pass": ms, "bytes_per_pass": bytes_pass, "GBps": gbs, "peak_GBps": HBM_PEAK_GBS,
+            "frac": gbs / HBM_PEAK_GBS}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cifar_mlp", choices=[k for k, v in WORKLOADS.items() if v.dims])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-meta-only", action="store_true")
+    ap.add_argument("--cpu-learners", type=int, default=3)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device copy (reference dispatch for scaling rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (all P learners on one MI355X); --gpus %d is not "
+              "supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    kavg.load_library()
+    w = WORKLOADS[args.workload]
+    data = synth.make_workload_inputs(w)
+    bf = w.dtype == kavg.KAVG_BF16
+
+    g = kavg.MAvg(w.P, w.K, w.lr, w.mu, w.dims, w.B, w.dtype, index_seed=w.seeds["index"])
+    X = torch.from_numpy(data["Xbits"].view(np.int16) if bf else data["X32"]).cuda()
+    y = torch.from_numpy(data["y"]).cuda()
+    g.set_data(X, y)
+    g.set_params(data["w0"])
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                  # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        del src, dst
+
+    # warm-up rounds, every kernel class bracketed: gives the per-class breakdown
+    classes = ["index", "forward", "loss", "backward", "update", "meta"]
+    g.profile(classes)
+    for _ in range(max(args.warmup, 1)):
+        g.local_steps()
+        g.meta_update()
+    breakdown = g.profile_read()
+    heavy = max(("forward", "backward", "update", "meta"), key=lambda c: breakdown[c][0])
+
+    # timed region: only the dominant class carries events
+    g.profile([heavy])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        g.local_steps()
+        g.meta_update()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = g.profile_read()
+    g.profile([])
+    loss_last = float(g.losses()[-1].mean())
+
+    samples = w.P * w.K * w.B * args.steps
+    by, fl = class_model(w)
+    ms_heavy, launches = prof[heavy]
+    per_round = w.K if heavy != "meta" else 1
+    bytes_heavy = by[heavy] * per_round * args.steps           # all launches of the class in the timed region
+    flops_heavy = fl[heavy] * per_round * args.steps
+    t_hbm = bytes_heavy / (HBM_PEAK_GBS * 1e9)
+    peak_flops = (MFMA_BF16_PEAK_TFLOPS if bf else FP32_PEAK_TFLOPS) * 1e12
+    t_mfma = flops_heavy / peak_flops
+    traffic = stored_traffic(heavy)
+    if t_hbm >= t_mfma or heavy == "meta":
+        achieved = bytes_heavy / (ms_heavy * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS}
+    else:
+        achieved = flops_heavy / (ms_heavy * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": peak_flops / 1e12, "unit": "TFLOP/s",
+                "frac": achieved / (peak_flops / 1e12)}
+    roof.update({"traffic": traffic, "kernel_class": heavy, "launches": launches,
+                 "avg_launch_us": 1e3 * ms_heavy / max(launches, 1),
+                 "algorithmic_bytes_per_launch": bytes_heavy / max(launches, 1),
+                 "flops_per_launch": flops_heavy / max(launches, 1)})
+
+    # all dense products of the local steps against the matrix-core peak (context for the roofline)
+    gemm_ms = sum(breakdown[c][0] for c in ("forward", "backward", "update"))
+    gemm_flops = sum(fl[c] for c in ("forward", "backward", "update")) * w.K * max(args.warmup, 1)
+    local_mfma = {"achieved_TFLOPs": gemm_flops / (gemm_ms * 1e-3) / 1e12, "peak_TFLOPs": peak_flops / 1e12,
+                  "frac": gemm_flops / (gemm_ms * 1e-3) / peak_flops,
+                  "note": "forward+backward+update launches of the profiled warm-up rounds"}
+
+    out = {
+        "metric": "learner-samples/sec (all P on 1 GPU); meta-update GB/s vs HBM peak",
+        "value": samples / dt, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if bf else "f32", "data": "synthetic",
+        "config": {"workload": "%s: P=%d K=%d B=%d mu=%g lr=%g MLP %s, N=%d" % (
+            w.name, w.P, w.K, w.B, w.mu, w.lr, "-".join(map(str, w.dims)), w.N),
+            "step": "one meta round = K local steps on P learners + fused meta step",
+            "samples_per_step": w.P * w.K * w.B, "flops_per_step": flops_per_learner_step(w.dims, w.B) * w.P * w.K},
+        "roofline": roof,
+        "local_steps_mfma": local_mfma,
+        "kernel_ms_per_round": {c: breakdown[c][0] / max(args.warmup, 1) for c in classes},
+        "final_mean_loss": loss_last,
+    }
+    if not args.no_meta_only:
+        g.close()
+        del X, y
+        torch.cuda.empty_cache()
+        out["meta_update"] = bench_meta_only(torch)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, data, min(args.cpu_learners, w.P))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

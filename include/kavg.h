@@ -133,6 +133,23 @@ int kavg_losses(kavg_ctx* ctx, float* out_host);
 /* [P][K][B] indices used by the last kavg_local_steps */
 int kavg_indices(kavg_ctx* ctx, int32_t* out_host);
 
+/* Measurement aid for callers that report per-kernel time (not part of the
+ * method): while a class's bit is set in class_mask, every launch of that class
+ * is bracketed by a HIP event pair on the context's stream.  kavg_profile waits
+ * for the stream, clears the totals and installs the mask (0 = off);
+ * kavg_profile_read waits for the stream and returns, per class, the summed
+ * elapsed milliseconds and the number of launches since then
+ * (arrays of KAVG_NCLASS entries, host). */
+#define KAVG_CLASS_INDEX    0   /* minibatch index stream / import        */
+#define KAVG_CLASS_FORWARD  1   /* per-layer forward products              */
+#define KAVG_CLASS_LOSS     2   /* softmax cross-entropy + gradient, loss mean */
+#define KAVG_CLASS_BACKWARD 3   /* per-layer data gradients                */
+#define KAVG_CLASS_UPDATE   4   /* per-layer weight gradient + SGD update  */
+#define KAVG_CLASS_META     5   /* fused meta step                         */
+#define KAVG_NCLASS         6
+int kavg_profile(kavg_ctx* ctx, unsigned class_mask);
+int kavg_profile_read(kavg_ctx* ctx, double* ms_out, long long* launches_out);
+
 uint64_t    kavg_round(const kavg_ctx* ctx);
 const char* kavg_last_error(const kavg_ctx* ctx);   /* ctx == NULL: text of the last failed kavg_init */
 int         kavg_destroy(kavg_ctx* ctx);            /* waits for the stream, frees the host context  */

@@ -94,6 +94,12 @@ struct kavg_ctx {
     uint64_t round;
     bool have_params, have_steps;
     char err[256];
+    // measurement aid: HIP event pairs around the launches of selected kernel classes
+    unsigned prof_mask;
+    std::vector<hipEvent_t> prof_ev[KAVG_NCLASS];   // start/stop alternate
+    size_t prof_used[KAVG_NCLASS];
+    double prof_ms[KAVG_NCLASS];
+    long long prof_launches[KAVG_NCLASS];
 
     float* w_tilde() const { return (float*)(ws + lo.off_w); }
     float* v() const { return (float*)(ws + lo.off_v); }
@@ -149,6 +155,26 @@ int install_global(kavg_ctx* c, const float* w_host, const float* v_host) {
     c->have_steps = false;
     return KAVG_OK;
 }
+
+// Brackets one launch with an event pair when its class is being profiled.
+struct Bracket {
+    kavg_ctx* c; int cls; bool on; hipEvent_t stop;
+    Bracket(kavg_ctx* ctx, int k) : c(ctx), cls(k), on(false), stop(nullptr) {
+        if (!(c->prof_mask & (1u << cls))) return;
+        std::vector<hipEvent_t>& pool = c->prof_ev[cls];
+        while (pool.size() < c->prof_used[cls] + 2) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return;
+            pool.push_back(e);
+        }
+        hipEvent_t start = pool[c->prof_used[cls]];
+        stop = pool[c->prof_used[cls] + 1];
+        if (hipEventRecord(start, c->stream) != hipSuccess) return;
+        c->prof_used[cls] += 2;
+        on = true;
+    }
+    ~Bracket() { if (on) (void)hipEventRecord(stop, c->stream); }
+};
 
 LayerCall layer_call(const kavg_ctx* c, int l /*1..L*/, int k) {
     const Layout& lo = c->lo;
@@ -225,6 +251,8 @@ int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, co
     c->X = nullptr; c->y = nullptr; c->N = 0; c->user_idx = nullptr;
     c->t0 = 0; c->round = 0; c->have_params = false; c->have_steps = false;
     c->err[0] = 0;
+    c->prof_mask = 0;
+    for (int k = 0; k < KAVG_NCLASS; ++k) { c->prof_used[k] = 0; c->prof_ms[k] = 0.0; c->prof_launches[k] = 0; }
     hipError_t e = hipMemsetAsync(c->flag(), 0, ALIGN, c->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) {
@@ -280,27 +308,41 @@ int kavg_local_steps(kavg_ctx* c) {
     hipStream_t st = c->stream;
     const bool bf = c->dtype == KAVG_BF16;
     const int L = c->L;
-    if (c->user_idx)
-        KAVG_HIP(c, launch_index_import(c->idx(), c->user_idx, (size_t)c->P * c->K * c->B, (uint32_t)c->N,
-                                        c->flag(), st));
-    else
-        KAVG_HIP(c, launch_index_stream(c->idx(), c->P, c->K, c->B, c->seed, c->t0, (uint32_t)c->N, st));
+    {
+        Bracket br(c, KAVG_CLASS_INDEX);
+        if (c->user_idx)
+            KAVG_HIP(c, launch_index_import(c->idx(), c->user_idx, (size_t)c->P * c->K * c->B, (uint32_t)c->N,
+                                            c->flag(), st));
+        else
+            KAVG_HIP(c, launch_index_stream(c->idx(), c->P, c->K, c->B, c->seed, c->t0, (uint32_t)c->N, st));
+    }
 
     for (int k = 0; k < c->K; ++k) {
         for (int l = 1; l <= L; ++l) {                       // forward
             LayerCall q = layer_call(c, l, k);
+            Bracket br(c, KAVG_CLASS_FORWARD);
             KAVG_HIP(c, bf ? bf16_forward(q, st) : f32_forward(q, st));
         }
+        {
+        Bracket br(c, KAVG_CLASS_LOSS);
         KAVG_HIP(c, launch_softmax_ce(c->logits(), c->lo.ldz, c->dims[L], c->y, c->idx() + (size_t)k * c->B,
                                       (long)c->K * c->B, c->B, c->P, c->ws + c->lo.off_dz[L - 1], bf ? 1 : 0,
                                       c->rowloss() + (size_t)k * c->P * c->B, st));
+        }
         for (int l = L; l >= 1; --l) {                       // backward; W_l is read before it is updated
             LayerCall q = layer_call(c, l, k);
-            if (l > 1) KAVG_HIP(c, bf ? bf16_backward_data(q, st) : f32_backward_data(q, st));
+            if (l > 1) {
+                Bracket br(c, KAVG_CLASS_BACKWARD);
+                KAVG_HIP(c, bf ? bf16_backward_data(q, st) : f32_backward_data(q, st));
+            }
+            Bracket br(c, KAVG_CLASS_UPDATE);
             KAVG_HIP(c, bf ? bf16_update(q, st) : f32_update(q, st));
         }
     }
-    KAVG_HIP(c, launch_loss_mean(c->rowloss(), c->losses(), c->K * c->P, c->B, st));
+    {
+        Bracket br(c, KAVG_CLASS_LOSS);
+        KAVG_HIP(c, launch_loss_mean(c->rowloss(), c->losses(), c->K * c->P, c->B, st));
+    }
     c->t0 += (uint32_t)c->K;
     c->have_steps = true;
     return KAVG_OK;
@@ -309,8 +351,11 @@ int kavg_local_steps(kavg_ctx* c) {
 int kavg_meta_update(kavg_ctx* c) {
     if (!c) return KAVG_EINVAL;
     if (!c->have_params) return fail(c, KAVG_ESTATE, "no parameters: call kavg_set_params first");
-    KAVG_HIP(c, launch_meta_update(c->w_tilde(), c->v(), c->reps(), c->lo.stride, c->shadow(), c->lo.stride,
-                                   c->P, c->lo.n, c->mu, c->stream));
+    {
+        Bracket br(c, KAVG_CLASS_META);
+        KAVG_HIP(c, launch_meta_update(c->w_tilde(), c->v(), c->reps(), c->lo.stride, c->shadow(), c->lo.stride,
+                                       c->P, c->lo.n, c->mu, c->stream));
+    }
     c->round += 1;
     return KAVG_OK;
 }
@@ -356,6 +401,39 @@ int kavg_indices(kavg_ctx* c, int32_t* out_host) {
     return copy_out(c, c->idx(), out_host, (size_t)c->P * c->K * c->B * 4);
 }
 
+static int prof_drain(kavg_ctx* c) {
+    KAVG_HIP(c, hipStreamSynchronize(c->stream));
+    for (int k = 0; k < KAVG_NCLASS; ++k) {
+        for (size_t i = 0; i + 1 < c->prof_used[k]; i += 2) {
+            float ms = 0.f;
+            KAVG_HIP(c, hipEventElapsedTime(&ms, c->prof_ev[k][i], c->prof_ev[k][i + 1]));
+            c->prof_ms[k] += ms;
+            c->prof_launches[k] += 1;
+        }
+        c->prof_used[k] = 0;
+    }
+    return KAVG_OK;
+}
+
+int kavg_profile(kavg_ctx* c, unsigned class_mask) {
+    if (!c) return KAVG_EINVAL;
+    if (class_mask >> KAVG_NCLASS) return fail(c, KAVG_EINVAL, "unknown kernel class in mask");
+    int rc = prof_drain(c);
+    if (rc != KAVG_OK) return rc;
+    for (int k = 0; k < KAVG_NCLASS; ++k) { c->prof_ms[k] = 0.0; c->prof_launches[k] = 0; }
+    c->prof_mask = class_mask;
+    return KAVG_OK;
+}
+
+int kavg_profile_read(kavg_ctx* c, double* ms_out, long long* launches_out) {
+    if (!c) return KAVG_EINVAL;
+    if (!ms_out || !launches_out) return fail(c, KAVG_EINVAL, "null output");
+    int rc = prof_drain(c);
+    if (rc != KAVG_OK) return rc;
+    for (int k = 0; k < KAVG_NCLASS; ++k) { ms_out[k] = c->prof_ms[k]; launches_out[k] = c->prof_launches[k]; }
+    return KAVG_OK;
+}
+
 uint64_t kavg_round(const kavg_ctx* c) { return c ? c->round : 0; }
 
 const char* kavg_last_error(const kavg_ctx* c) { return c ? c->err : g_init_error; }
@@ -363,6 +441,8 @@ const char* kavg_last_error(const kavg_ctx* c) { return c ? c->err : g_init_erro
 int kavg_destroy(kavg_ctx* c) {
     if (!c) return KAVG_EINVAL;
     hipError_t e = hipStreamSynchronize(c->stream);
+    for (int k = 0; k < KAVG_NCLASS; ++k)
+        for (hipEvent_t ev : c->prof_ev[k]) (void)hipEventDestroy(ev);
     delete c;
     return e == hipSuccess ? KAVG_OK : KAVG_EDEVICE;
 }

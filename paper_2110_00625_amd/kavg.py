@@ -19,8 +19,9 @@ EXPORTS = [
     "kavg_num_params", "kavg_workspace_bytes", "kavg_init", "kavg_set_params", "kavg_set_state",
     "kavg_set_data", "kavg_set_indices", "kavg_local_steps", "kavg_meta_update", "kavg_params",
     "kavg_momentum", "kavg_replica", "kavg_losses", "kavg_indices", "kavg_round", "kavg_last_error",
-    "kavg_destroy", "kavg_meta_update_flat",
+    "kavg_destroy", "kavg_meta_update_flat", "kavg_profile", "kavg_profile_read",
 ]
+CLASS_NAMES = ["index", "forward", "loss", "backward", "update", "meta"]
 
 
 class KavgError(RuntimeError):
@@ -37,6 +38,10 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
+    # PyTorch owns the device memory and the stream this library works on, so both must
+    # talk to ONE HIP runtime: import torch first, its libamdhip64 is then the one
+    # libkavg.so binds to (same SONAME) instead of a second copy from the ROCm tree.
+    import torch  # noqa: F401
     if not os.path.exists(LIB_PATH):
         raise FileNotFoundError(
             "%s not found: build it with `python -m paper_2110_00625_amd.build`" % LIB_PATH)
@@ -63,6 +68,8 @@ def load_library():
         "kavg_losses": [c_vp, c_vp],
         "kavg_indices": [c_vp, c_vp],
         "kavg_destroy": [c_vp],
+        "kavg_profile": [c_vp, ctypes.c_uint],
+        "kavg_profile_read": [c_vp, c_vp, c_vp],
         "kavg_meta_update_flat": [c_vp, c_vp, c_vp, c_sz, c_vp, c_sz, c_int, c_sz, c_f, c_vp],
     }.items():
         fn = getattr(lib, name)
@@ -199,6 +206,20 @@ class MAvg:
         out = np.empty((self.P, self.K, self.B), dtype=np.int32)
         _check(self.lib, self.ctx, self.lib.kavg_indices(self.ctx, out.ctypes.data))
         return out
+
+    def profile(self, classes):
+        """Bracket the launches of the named kernel classes with HIP events (() = off)."""
+        mask = 0
+        for name in classes:
+            mask |= 1 << CLASS_NAMES.index(name)
+        _check(self.lib, self.ctx, self.lib.kavg_profile(self.ctx, mask))
+
+    def profile_read(self):
+        """{class: (total ms, launches)} since the last profile() call."""
+        ms = (ctypes.c_double * len(CLASS_NAMES))()
+        cnt = (ctypes.c_longlong * len(CLASS_NAMES))()
+        _check(self.lib, self.ctx, self.lib.kavg_profile_read(self.ctx, ms, cnt))
+        return {n: (ms[i], int(cnt[i])) for i, n in enumerate(CLASS_NAMES)}
 
     def round(self):
         return int(self.lib.kavg_round(self.ctx))
