@@ -21,11 +21,15 @@
 //
 // An operand whose contraction index is contiguous in memory ("direct": the
 // activations and weights of the forward pass, dZ of backward-data) is copied
-// to LDS in 16-byte pieces.  An operand whose contraction index is the row
-// index in memory ("transposed": W in backward-data, dZ and A in the update,
-// whose contraction runs over the samples) is loaded as 4x8 blocks with
-// coalesced 16-byte row reads, transposed in registers, and written as 8-byte
-// pieces, so that LDS always holds [row][k] with k contiguous.
+// to LDS as [x][k] in 16-byte pieces and read back as 16-byte MFMA fragments.
+// An operand whose contraction index is the row index in memory ("transposed":
+// W in backward-data, dZ and A in the update, whose contraction runs over the
+// samples) is copied to LDS unchanged as [k][x], again in 16-byte pieces, and
+// its MFMA fragments are produced by the LDS transpose read
+// (ds_read_b64_tr_b16): inside a 16-lane group the lanes fetch a 4(k) x 16(x)
+// block, four consecutive x per lane, and each lane receives the four k of
+// one x.  Both LDS layouts are padded so that fragment reads and tile writes
+// spread over all banks.
 //
 // Rows beyond an extent are zero-filled on load and masked on store; every
 // memory-contiguous extent is a multiple of 8 elements (hidden widths are
@@ -61,6 +65,7 @@ struct Operand {
 struct Args {
     Operand R, C;
     int nR, nC, nK;
+    int tiles_r, tiles_c, total_wg, chunk;       // workgroup -> tile map (see tile_of)
     // forward
     const float* bias; size_t bias_lstride;
     void* out; size_t out_lstride; int ld_out;   // bf16 activations or fp32 logits
@@ -84,11 +89,14 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t h) {
 }
 
 // ---- staging: global -> registers -> LDS ------------------------------------
-template <int X> struct DirectRegs { u32x4 v[X / 32]; };
-template <int X> struct TransRegs  { u32x4 v[4]; };     // four memory rows (k), eight x each
+// Every thread moves X/32 pieces of 16 bytes per operand and slice.
+template <int X> struct StageRegs { u32x4 v[X / 32]; };
 
+constexpr int tpitch(int X) { return X + 32; }     // [k][x] tile: row of X bf16 plus 64 bytes
+
+// direct operand: piece e covers memory row x0 + e/8, k0 + 8*(e%8) .. +7
 template <int X>
-__device__ __forceinline__ void load_direct(DirectRegs<X>& g, const Operand& o, const uint16_t* base,
+__device__ __forceinline__ void load_direct(StageRegs<X>& g, const Operand& o, const uint16_t* base,
                                             const int32_t* gather, int x0, int k0, int tid) {
 #pragma unroll
     for (int i = 0; i < X / 32; ++i) {
@@ -104,7 +112,7 @@ __device__ __forceinline__ void load_direct(DirectRegs<X>& g, const Operand& o, 
 }
 
 template <int X>
-__device__ __forceinline__ void store_direct(const DirectRegs<X>& g, uint16_t* lds, int tid) {
+__device__ __forceinline__ void store_direct(const StageRegs<X>& g, uint16_t* lds, int tid) {
 #pragma unroll
     for (int i = 0; i < X / 32; ++i) {
         const int e = tid + 256 * i;
@@ -112,44 +120,50 @@ __device__ __forceinline__ void store_direct(const DirectRegs<X>& g, uint16_t* l
     }
 }
 
-// thread u of X/8 * 16 handles memory rows k0 + 4*(u / (X/8)) .. +3 and columns x0 + 8*(u % (X/8)) .. +7
+// transposed operand: piece e covers memory row k0 + e/(X/8), columns x0 + 8*(e%(X/8)) .. +7
 template <int X>
-__device__ __forceinline__ void load_trans(TransRegs<X>& g, const Operand& o, const uint16_t* base,
+__device__ __forceinline__ void load_trans(StageRegs<X>& g, const Operand& o, const uint16_t* base,
                                            const int32_t* gather, int x0, int k0, int tid) {
-    constexpr int XB = X / 8;
-    const int xb = tid % XB, kb = tid / XB;
-    const int x = x0 + xb * 8;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int k = k0 + kb * 4 + r;
+    for (int i = 0; i < X / 32; ++i) {
+        const int e = tid + 256 * i;
+        const int k = k0 + e / (X / 8), x = x0 + (e % (X / 8)) * 8;
         u32x4 val = {0u, 0u, 0u, 0u};
-        if (kb < 16 && k < o.n_rows && x < o.n_cont) {
+        if (k < o.n_rows && x < o.n_cont) {
             const long row = gather ? (long)gather[k] : (long)k;
             val = *(const u32x4*)(base + row * o.ld + x);
         }
-        g.v[r] = val;
+        g.v[i] = val;
     }
 }
 
 template <int X>
-__device__ __forceinline__ void store_trans(const TransRegs<X>& g, uint16_t* lds, int tid) {
-    constexpr int XB = X / 8;
-    const int xb = tid % XB, kb = tid / XB;
-    if (kb >= 16) return;
+__device__ __forceinline__ void store_trans(const StageRegs<X>& g, uint16_t* lds, int tid) {
 #pragma unroll
-    for (int xi = 0; xi < 8; ++xi) {
-        const int w = xi >> 1;
-        uint32_t lo, hi;
-        if (xi & 1) {
-            lo = (g.v[0][w] >> 16) | (g.v[1][w] & 0xFFFF0000u);
-            hi = (g.v[2][w] >> 16) | (g.v[3][w] & 0xFFFF0000u);
-        } else {
-            lo = (g.v[0][w] & 0xFFFFu) | (g.v[1][w] << 16);
-            hi = (g.v[2][w] & 0xFFFFu) | (g.v[3][w] << 16);
-        }
-        u32x2 out = {lo, hi};
-        *(u32x2*)(lds + (xb * 8 + xi) * BKP + kb * 4) = out;
+    for (int i = 0; i < X / 32; ++i) {
+        const int e = tid + 256 * i;
+        *(u32x4*)(lds + (e / (X / 8)) * tpitch(X) + (e % (X / 8)) * 8) = g.v[i];
     }
+}
+
+// MFMA fragment (lane l: index l%32 of the 32-block, k = 8*(l/32) .. +7 of the 16-slab)
+__device__ __forceinline__ bf16x8 frag_direct(const uint16_t* tile, int block_row0, int kk, int lane) {
+    return *(const bf16x8*)(tile + (block_row0 + (lane & 31)) * BKP + kk * 16 + (lane >> 5) * 8);
+}
+
+// Same fragment out of a [k][x] tile with two transpose reads.  In its 16-lane group, lane t = 4a + b
+// fetches x = 4b .. 4b+3 of row k = a and receives the four k (a = 0..3) of x = t.
+template <int X>
+__device__ __forceinline__ bf16x8 frag_trans(const uint16_t* tile, int block_x0, int kk, int lane) {
+    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+    const int t = lane & 15, grp = lane >> 4;
+    const int krow = kk * 16 + (grp >> 1) * 8 + (t >> 2);
+    const int xcol = block_x0 + (grp & 1) * 16 + (t & 3) * 4;
+    const uint16_t* p = tile + krow * tpitch(X) + xcol;
+    typedef bf16x4 __attribute__((address_space(3))) * lds_ptr;
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)p);
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr)(p + 4 * tpitch(X)));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
 // ---- the kernel ----------------------------------------------------------------
@@ -159,13 +173,30 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(Args a) {
     static_assert(WR * WC == 4, "four wavefronts per workgroup");
     constexpr int MR = TR / (32 * WR), MC = TC / (32 * WC);
     static_assert(MR >= 1 && MC >= 1, "tile too small for the wave grid");
-    __shared__ __attribute__((aligned(16))) uint16_t Rs[TR * BKP];
-    __shared__ __attribute__((aligned(16))) uint16_t Cs[TC * BKP];
+    // update epilogue: each wavefront turns one 32-row block of its accumulators into rows in LDS
+    constexpr int WTC = MC * 32;                 // columns of a wavefront's tile
+    constexpr int SPITCH = WTC + 4;              // fp32 staging row, padded
+    constexpr int R_ELEMS = RTRANS ? BK * tpitch(TR) : TR * BKP;
+    constexpr int C_ELEMS = CTRANS ? BK * tpitch(TC) : TC * BKP;
+    constexpr int OPER_BYTES = (R_ELEMS + C_ELEMS) * 2;
+    constexpr int STAGE_BYTES = MODE == MODE_UPD ? 4 * 32 * SPITCH * 4 : 0;
+    constexpr int SMEM_BYTES = OPER_BYTES > STAGE_BYTES ? OPER_BYTES : STAGE_BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
+    uint16_t* Rs = (uint16_t*)smem;
+    uint16_t* Cs = Rs + R_ELEMS;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave / WC, wc = wave % WC;
-    const int learner = blockIdx.z;
-    const int r0 = blockIdx.y * TR, c0 = blockIdx.x * TC;
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2) in launch order, so
+    // workgroup g runs on XCD g%8.  Give every XCD one contiguous range of the logical order
+    // (learner, row tile, column tile): the tiles of a learner then share that learner's operands
+    // through a single L2 instead of pulling them into all eight.
+    const int logical = (int)(blockIdx.x & 7) * a.chunk + (int)(blockIdx.x >> 3);
+    if (logical >= a.total_wg) return;
+    const int learner = logical / (a.tiles_r * a.tiles_c);
+    const int tile = logical - learner * (a.tiles_r * a.tiles_c);
+    const int tile_r = tile / a.tiles_c, tile_c = tile - tile_r * a.tiles_c;
+    const int r0 = tile_r * TR, c0 = tile_c * TC;
 
     const uint16_t* Rbase = a.R.base + (size_t)learner * a.R.lstride;
     const uint16_t* Cbase = a.C.base + (size_t)learner * a.C.lstride;
@@ -180,17 +211,17 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(Args a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    DirectRegs<TR> rd; TransRegs<TR> rt;
-    DirectRegs<TC> cd; TransRegs<TC> ct;
+    StageRegs<TR> rg;
+    StageRegs<TC> cg;
     float bias_sum = 0.f;                       // update: column sum of dZ for row r0 + tid
 
     auto fetch = [&](int k0) {
-        if (RTRANS) load_trans<TR>(rt, a.R, Rbase, Rg, r0, k0, tid); else load_direct<TR>(rd, a.R, Rbase, Rg, r0, k0, tid);
-        if (CTRANS) load_trans<TC>(ct, a.C, Cbase, Cg, c0, k0, tid); else load_direct<TC>(cd, a.C, Cbase, Cg, c0, k0, tid);
+        if (RTRANS) load_trans<TR>(rg, a.R, Rbase, Rg, r0, k0, tid); else load_direct<TR>(rg, a.R, Rbase, Rg, r0, k0, tid);
+        if (CTRANS) load_trans<TC>(cg, a.C, Cbase, Cg, c0, k0, tid); else load_direct<TC>(cg, a.C, Cbase, Cg, c0, k0, tid);
     };
     auto stash = [&]() {
-        if (RTRANS) store_trans<TR>(rt, Rs, tid); else store_direct<TR>(rd, Rs, tid);
-        if (CTRANS) store_trans<TC>(ct, Cs, tid); else store_direct<TC>(cd, Cs, tid);
+        if (RTRANS) store_trans<TR>(rg, Rs, tid); else store_direct<TR>(rg, Rs, tid);
+        if (CTRANS) store_trans<TC>(cg, Cs, tid); else store_direct<TC>(cg, Cs, tid);
     };
 
     fetch(0);
@@ -201,84 +232,127 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(Args a) {
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8 cf[MC], rf[MR];
-            const int koff = kk * 16 + (lane >> 5) * 8;
 #pragma unroll
             for (int j = 0; j < MC; ++j)
-                cf[j] = *(const bf16x8*)(Cs + (wc * MC * 32 + j * 32 + (lane & 31)) * BKP + koff);
+                cf[j] = CTRANS ? frag_trans<TC>(Cs, (wc * MC + j) * 32, kk, lane)
+                               : frag_direct(Cs, (wc * MC + j) * 32, kk, lane);
 #pragma unroll
             for (int i = 0; i < MR; ++i)
-                rf[i] = *(const bf16x8*)(Rs + (wr * MR * 32 + i * 32 + (lane & 31)) * BKP + koff);
+                rf[i] = RTRANS ? frag_trans<TR>(Rs, (wr * MR + i) * 32, kk, lane)
+                               : frag_direct(Rs, (wr * MR + i) * 32, kk, lane);
 #pragma unroll
             for (int i = 0; i < MR; ++i)
 #pragma unroll
                 for (int j = 0; j < MC; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf[j], rf[i], acc[i][j], 0, 0, 0);
         }
-        if (MODE == MODE_UPD && blockIdx.x == 0 && tid < TR) {
-            const uint16_t* row = Rs + tid * BKP;
+        if (MODE == MODE_UPD && tile_c == 0 && tid < TR) {
+            // R tile of the update is dZ as [sample][unit]: column tid summed over the slice's samples
 #pragma unroll 8
-            for (int k = 0; k < BK; ++k) bias_sum += bf16_to_f32(row[k]);
+            for (int k = 0; k < BK; ++k) bias_sum += bf16_to_f32(Rs[k * tpitch(TR) + tid]);
         }
         __syncthreads();
     }
 
     // ---- epilogue: lane owns, per block, row r = l%32 and columns 8q + 4(l/32) + 0..3, q = 0..3
+    if (MODE != MODE_UPD) {
 #pragma unroll
-    for (int i = 0; i < MR; ++i) {
-        const int r = r0 + (wr * MR + i) * 32 + (lane & 31);
-        if (r >= a.nR) continue;
+        for (int i = 0; i < MR; ++i) {
+            const int r = r0 + (wr * MR + i) * 32 + (lane & 31);
+            if (r >= a.nR) continue;
 #pragma unroll
-        for (int j = 0; j < MC; ++j) {
+            for (int j = 0; j < MC; ++j) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int c = c0 + (wc * MC + j) * 32 + q * 8 + (lane >> 5) * 4;
-                float v0 = acc[i][j][4 * q + 0], v1 = acc[i][j][4 * q + 1];
-                float v2 = acc[i][j][4 * q + 2], v3 = acc[i][j][4 * q + 3];
-                if (MODE == MODE_FWD) {
-                    if (c >= a.ld_out) continue;
-                    const float* bias = a.bias + (size_t)learner * a.bias_lstride;
-                    v0 += c + 0 < a.nC ? bias[c + 0] : 0.f;
-                    v1 += c + 1 < a.nC ? bias[c + 1] : 0.f;
-                    v2 += c + 2 < a.nC ? bias[c + 2] : 0.f;
-                    v3 += c + 3 < a.nC ? bias[c + 3] : 0.f;
-                    if (a.relu) {
-                        u32x2 o = {pack2(fmaxf(v0, 0.f), fmaxf(v1, 0.f)), pack2(fmaxf(v2, 0.f), fmaxf(v3, 0.f))};
-                        *(u32x2*)((uint16_t*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
+                for (int q = 0; q < 4; ++q) {
+                    const int c = c0 + (wc * MC + j) * 32 + q * 8 + (lane >> 5) * 4;
+                    float v0 = acc[i][j][4 * q + 0], v1 = acc[i][j][4 * q + 1];
+                    float v2 = acc[i][j][4 * q + 2], v3 = acc[i][j][4 * q + 3];
+                    if (MODE == MODE_FWD) {
+                        if (c >= a.ld_out) continue;
+                        const float* bias = a.bias + (size_t)learner * a.bias_lstride;
+                        v0 += c + 0 < a.nC ? bias[c + 0] : 0.f;
+                        v1 += c + 1 < a.nC ? bias[c + 1] : 0.f;
+                        v2 += c + 2 < a.nC ? bias[c + 2] : 0.f;
+                        v3 += c + 3 < a.nC ? bias[c + 3] : 0.f;
+                        if (a.relu) {
+                            u32x2 o = {pack2(fmaxf(v0, 0.f), fmaxf(v1, 0.f)), pack2(fmaxf(v2, 0.f), fmaxf(v3, 0.f))};
+                            *(u32x2*)((uint16_t*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
+                        } else {
+                            f32x4 o = {v0, v1, v2, v3};
+                            *(f32x4*)((float*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
+                        }
                     } else {
-                        f32x4 o = {v0, v1, v2, v3};
-                        *(f32x4*)((float*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
+                        if (c >= a.nC) continue;
+                        const u32x2 m = *(const u32x2*)(a.act_prev + (size_t)learner * a.act_lstride + (size_t)r * a.ld_act + c);
+                        // stored activations are relu outputs (never negative): positive <=> non-zero magnitude
+                        v0 = (m.x & 0x7FFFu) ? v0 : 0.f;
+                        v1 = (m.x & 0x7FFF0000u) ? v1 : 0.f;
+                        v2 = (m.y & 0x7FFFu) ? v2 : 0.f;
+                        v3 = (m.y & 0x7FFF0000u) ? v3 : 0.f;
+                        u32x2 o = {pack2(v0, v1), pack2(v2, v3)};
+                        *(u32x2*)((uint16_t*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
                     }
-                } else if (MODE == MODE_BWD) {
-                    if (c >= a.nC) continue;
-                    const u32x2 m = *(const u32x2*)(a.act_prev + (size_t)learner * a.act_lstride + (size_t)r * a.ld_act + c);
-                    // stored activations are relu outputs (never negative): positive <=> non-zero magnitude
-                    v0 = (m.x & 0x7FFFu) ? v0 : 0.f;
-                    v1 = (m.x & 0x7FFF0000u) ? v1 : 0.f;
-                    v2 = (m.y & 0x7FFFu) ? v2 : 0.f;
-                    v3 = (m.y & 0x7FFF0000u) ? v3 : 0.f;
-                    u32x2 o = {pack2(v0, v1), pack2(v2, v3)};
-                    *(u32x2*)((uint16_t*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
-                } else {
-                    if (c >= a.nC) continue;
-                    float* wp = a.w + (size_t)learner * a.w_lstride + (size_t)r * a.nC + c;
-                    f32x4 w = *(const f32x4*)wp;
-                    w.x -= a.lr * v0; w.y -= a.lr * v1; w.z -= a.lr * v2; w.w -= a.lr * v3;
-                    *(f32x4*)wp = w;
-                    u32x2 o = {pack2(w.x, w.y), pack2(w.z, w.w)};
-                    *(u32x2*)(a.ws + (size_t)learner * a.ws_lstride + (size_t)r * a.nC + c) = o;
                 }
             }
         }
-    }
-    if (MODE == MODE_UPD && blockIdx.x == 0 && tid < TR && r0 + tid < a.nR) {
-        float* b = a.b + (size_t)learner * a.w_lstride + r0 + tid;
-        *b = *b - a.lr * bias_sum;
+    } else {
+        // Update: the master tile is read and written as whole row segments.  Each wavefront passes one
+        // 32-row block of its accumulators through a private LDS patch so that a lane ends up with four
+        // consecutive columns of a row and 64/(WTC/4) rows are covered per access, WTC*4 contiguous bytes each.
+        constexpr int F4_PER_ROW = WTC / 4;
+        constexpr int ROWS_PER_IT = 64 / F4_PER_ROW;
+        constexpr int ITS = 32 / ROWS_PER_IT;
+        float* stage = (float*)smem + wave * 32 * SPITCH;
+        float* wbase = a.w + (size_t)learner * a.w_lstride;
+        uint16_t* sbase = a.ws + (size_t)learner * a.ws_lstride;
+        const int rr = lane / F4_PER_ROW, cc = (lane % F4_PER_ROW) * 4;
+        const int c = c0 + wc * WTC + cc;
+#pragma unroll
+        for (int i = 0; i < MR; ++i) {
+            const int rblk = r0 + (wr * MR + i) * 32;
+            f32x4 m[ITS];
+#pragma unroll
+            for (int it = 0; it < ITS; ++it) {          // master loads go out before the LDS shuffle
+                const int r = rblk + it * ROWS_PER_IT + rr;
+                m[it] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                if (r < a.nR && c < a.nC) m[it] = *(const f32x4*)(wbase + (size_t)r * a.nC + c);
+            }
+            __syncthreads();                            // previous patch contents (or operand tiles) are dead
+#pragma unroll
+            for (int j = 0; j < MC; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    f32x4 v = {acc[i][j][4 * q + 0], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                    *(f32x4*)(stage + (lane & 31) * SPITCH + j * 32 + q * 8 + (lane >> 5) * 4) = v;
+                }
+            __syncthreads();
+#pragma unroll
+            for (int it = 0; it < ITS; ++it) {
+                const int r = rblk + it * ROWS_PER_IT + rr;
+                const f32x4 g = *(const f32x4*)(stage + (it * ROWS_PER_IT + rr) * SPITCH + cc);
+                if (r < a.nR && c < a.nC) {
+                    f32x4 w = m[it];
+                    w.x -= a.lr * g.x; w.y -= a.lr * g.y; w.z -= a.lr * g.z; w.w -= a.lr * g.w;
+                    *(f32x4*)(wbase + (size_t)r * a.nC + c) = w;
+                    u32x2 o = {pack2(w.x, w.y), pack2(w.z, w.w)};
+                    *(u32x2*)(sbase + (size_t)r * a.nC + c) = o;
+                }
+            }
+        }
+        if (tile_c == 0 && tid < TR && r0 + tid < a.nR) {
+            float* b = a.b + (size_t)learner * a.w_lstride + r0 + tid;
+            *b = *b - a.lr * bias_sum;
+        }
     }
 }
 
 template <int MODE, int TR, int TC, int WR, int WC, bool RT, bool CT>
-hipError_t launch(const Args& a, int P, hipStream_t st) {
-    dim3 grid((a.nC + TC - 1) / TC, (a.nR + TR - 1) / TR, P);
+hipError_t launch(Args a, int P, hipStream_t st) {
+    a.tiles_c = (a.nC + TC - 1) / TC;
+    a.tiles_r = (a.nR + TR - 1) / TR;
+    a.total_wg = a.tiles_c * a.tiles_r * P;
+    a.chunk = (a.total_wg + 7) / 8;
+    dim3 grid(8 * a.chunk);
     hipLaunchKernelGGL((gemm_bf16_kernel<MODE, TR, TC, WR, WC, RT, CT>), grid, dim3(256), 0, st, a);
     return hipGetLastError();
 }

@@ -74,3 +74,101 @@ def test_meta_only_workload_full_size_200_passes():
     closed = inp["w_tilde"].astype(np.float64) + v1 * (1 - w.mu ** w.rounds) / (1 - w.mu)
     assert flat_error(got, closed) < 1e-4
     assert np.array_equal(reps[P - 1, :n].cpu().numpy(), got)
+
+
+# ---------------------------------------------------------------------------
+# bf16 workloads at their full shapes (P, K, B, layer widths as benchmarked).
+# The oracle cannot afford every learner of the two large ones, so:
+#  * learners are independent between meta steps, hence a SAMPLE of learners is
+#    walked through all K local steps by the oracle and compared with the same
+#    learners' replicas on the GPU (which ran all P);
+#  * the index stream of every learner is compared bit for bit;
+#  * the fused meta step is elementwise, so it is compared in full on seeded
+#    synthetic replicas of the workload's exact n, P and strides.
+# ---------------------------------------------------------------------------
+from paper_2110_00625_amd.configs import CIFAR_MLP, NOISY_WIDE, LARGE, num_params  # noqa: E402
+
+
+def _bf16_pair(w, N):
+    torch = _torch()
+    data = synth.make_workload_inputs(w, N=N)
+    g = kavg.MAvg(w.P, w.K, w.lr, w.mu, w.dims, w.B, kavg.KAVG_BF16, index_seed=w.seeds["index"])
+    g.set_data(torch.from_numpy(data["Xbits"].view(np.int16)).cuda(), torch.from_numpy(data["y"]).cuda())
+    g.set_params(data["w0"])
+    o = O.MAvgOracle(w.P, w.K, w.lr, w.mu, w.dims, w.B, bf16=True, index_seed=w.seeds["index"])
+    o.set_data(data["X32"], data["y"])
+    o.set_params(data["w0"])
+    return g, o
+
+
+def test_cifar_mlp_workload_free_running_rounds():
+    """P=16, K=8, B=128, MLP 3072-1024-1024-10, bf16 operands, N=50000: every learner,
+    global model compared after each of the first meta rounds (free running, no re-sync)."""
+    w = CIFAR_MLP
+    g, o = _bf16_pair(w, w.N)
+    for r in range(2):
+        g.local_steps()
+        o.local_steps()
+        assert np.array_equal(g.indices(), o.indices())
+        e = max(worst_error(g.replica(j), o.replica(j), w.dims) for j in (0, w.P - 1))
+        assert e < 2e-2, "replicas after local steps of round %d: %.3g" % (r, e)
+        assert np.max(np.abs(g.losses() - o.losses())) < 2e-2
+        g.meta_update()
+        o.meta_update()
+        e = worst_error(g.params(), o.params(), w.dims)
+        print("cifar_mlp round %d: max relative error %.3g" % (r, e))
+        assert e < 2e-2, "global model after round %d: %.3g" % (r, e)
+    g.close()
+
+
+@pytest.mark.parametrize("w,N,sample", [(NOISY_WIDE, 20000, (5,)), (LARGE, 20000, (7,))],
+                         ids=["noisy_wide", "large"])
+def test_large_workloads_sampled_learners(w, N, sample):
+    """Full P, K, B and layer widths; data set cut to N rows to keep host generation short
+    (N only sets the range of the gathered row indices)."""
+    g, o = _bf16_pair(w, N)
+    g.local_steps()
+    o.local_steps(learners=list(sample))
+    got_idx = g.indices()
+    for j in range(w.P):
+        for k in (0, w.K - 1):
+            assert np.array_equal(got_idx[j, k], O.minibatch_indices(w.seeds["index"], j, k, w.B, N))
+    for j in sample:
+        e = worst_error(g.replica(j), o.replica(j), w.dims)
+        print("%s learner %d after K=%d local steps: max relative error %.3g" % (w.name, j, w.K, e))
+        assert e < 2e-2
+        assert np.max(np.abs(g.losses()[:, j] - o.losses()[:, j])) < 2e-2
+    g.meta_update()
+    wt = g.params()
+    assert np.array_equal(g.replica(0), wt) and np.array_equal(g.replica(w.P - 1), wt)
+    g.close()
+
+
+@pytest.mark.parametrize("w", [CIFAR_MLP, NOISY_WIDE, LARGE], ids=lambda w: w.name)
+def test_meta_step_at_workload_size_with_shadows(w):
+    torch = _torch()
+    n, P = num_params(w.dims), w.P
+    stride = (n + 63) // 64 * 64
+    rng = np.random.default_rng(w.seeds["data"])
+    base = rng.standard_normal(n, dtype=np.float32) * np.float32(0.05)
+    v0 = rng.standard_normal(n, dtype=np.float32) * np.float32(1e-3)
+    wt = torch.from_numpy(base).cuda()
+    v = torch.from_numpy(v0).cuda()
+    reps = torch.empty((P, stride), device="cuda")
+    acc = np.zeros(n, dtype=np.float64)
+    for j in range(P):                                  # replica by replica: the oracle's sum in the same order
+        rj = base + rng.standard_normal(n, dtype=np.float32) * np.float32(1e-3)
+        reps[j, :n] = torch.from_numpy(rj).cuda()
+        acc += rj
+    sh = torch.zeros((P, stride), dtype=torch.int16, device="cuda")
+    kavg.kavg_meta_update_flat(wt, v, reps, w.mu, shadow=sh)
+    torch.cuda.synchronize()
+    a = acc * (1.0 / P)
+    vo = w.mu * v0.astype(np.float64) + (a - base)
+    wo = base + vo
+    got = wt.cpu().numpy()
+    assert flat_error(got, wo) < 1e-6
+    assert flat_error(v.cpu().numpy(), vo) < 1e-5
+    for j in (0, P - 1):
+        assert np.array_equal(reps[j, :n].cpu().numpy(), got)
+        assert np.array_equal(sh[j, :n].cpu().numpy().view(np.uint16), synth.snap_to_bf16_grid(got)[0])
