@@ -36,6 +36,10 @@
 // required to be, the class count is padded in the logits / dZ_L buffers).
 #include "kavg_internal.h"
 
+#ifndef KAVG_TILE_OVERRIDE
+#define KAVG_TILE_OVERRIDE(t) (t)
+#endif
+
 namespace kavg {
 
 namespace {
@@ -168,7 +172,8 @@ __device__ __forceinline__ bf16x8 frag_trans(const uint16_t* tile, int block_x0,
 
 // ---- the kernel ----------------------------------------------------------------
 // TR x TC output tile, 4 wavefronts arranged WR x WC, each owning MR x MC MFMA blocks of 32x32.
-template <int MODE, int TR, int TC, int WR, int WC, bool RTRANS, bool CTRANS>
+// S = slices kept in flight in registers ahead of the one being multiplied.
+template <int MODE, int TR, int TC, int WR, int WC, bool RTRANS, bool CTRANS, int S>
 __global__ void __launch_bounds__(256) gemm_bf16_kernel(Args a) {
     static_assert(WR * WC == 4, "four wavefronts per workgroup");
     constexpr int MR = TR / (32 * WR), MC = TC / (32 * WC);
@@ -211,47 +216,54 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(Args a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    StageRegs<TR> rg;
-    StageRegs<TC> cg;
+    StageRegs<TR> rg[S];
+    StageRegs<TC> cg[S];
     float bias_sum = 0.f;                       // update: column sum of dZ for row r0 + tid
 
-    auto fetch = [&](int k0) {
-        if (RTRANS) load_trans<TR>(rg, a.R, Rbase, Rg, r0, k0, tid); else load_direct<TR>(rg, a.R, Rbase, Rg, r0, k0, tid);
-        if (CTRANS) load_trans<TC>(cg, a.C, Cbase, Cg, c0, k0, tid); else load_direct<TC>(cg, a.C, Cbase, Cg, c0, k0, tid);
+    auto fetch = [&](StageRegs<TR>& r, StageRegs<TC>& c, int k0) {
+        if (RTRANS) load_trans<TR>(r, a.R, Rbase, Rg, r0, k0, tid); else load_direct<TR>(r, a.R, Rbase, Rg, r0, k0, tid);
+        if (CTRANS) load_trans<TC>(c, a.C, Cbase, Cg, c0, k0, tid); else load_direct<TC>(c, a.C, Cbase, Cg, c0, k0, tid);
     };
-    auto stash = [&]() {
-        if (RTRANS) store_trans<TR>(rg, Rs, tid); else store_direct<TR>(rg, Rs, tid);
-        if (CTRANS) store_trans<TC>(cg, Cs, tid); else store_direct<TC>(cg, Cs, tid);
+    auto stash = [&](const StageRegs<TR>& r, const StageRegs<TC>& c) {
+        if (RTRANS) store_trans<TR>(r, Rs, tid); else store_direct<TR>(r, Rs, tid);
+        if (CTRANS) store_trans<TC>(c, Cs, tid); else store_direct<TC>(c, Cs, tid);
     };
 
-    fetch(0);
-    for (int k0 = 0; k0 < a.nK; k0 += BK) {
-        stash();
-        __syncthreads();
-        if (k0 + BK < a.nK) fetch(k0 + BK);     // next slice in flight during the MFMAs
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 cf[MC], rf[MR];
+    for (int s = 0; s < S; ++s)
+        if (s * BK < a.nK) fetch(rg[s], cg[s], s * BK);
+    for (int kbase = 0; kbase < a.nK; kbase += S * BK) {
 #pragma unroll
-            for (int j = 0; j < MC; ++j)
-                cf[j] = CTRANS ? frag_trans<TC>(Cs, (wc * MC + j) * 32, kk, lane)
-                               : frag_direct(Cs, (wc * MC + j) * 32, kk, lane);
+        for (int s = 0; s < S; ++s) {
+            const int k0 = kbase + s * BK;
+            if (k0 >= a.nK) break;
+            stash(rg[s], cg[s]);
+            __syncthreads();
+            if (k0 + S * BK < a.nK) fetch(rg[s], cg[s], k0 + S * BK);   // S slices ahead, in flight during the MFMAs
 #pragma unroll
-            for (int i = 0; i < MR; ++i)
-                rf[i] = RTRANS ? frag_trans<TR>(Rs, (wr * MR + i) * 32, kk, lane)
-                               : frag_direct(Rs, (wr * MR + i) * 32, kk, lane);
-#pragma unroll
-            for (int i = 0; i < MR; ++i)
+            for (int kk = 0; kk < BK / 16; ++kk) {
+                bf16x8 cf[MC], rf[MR];
 #pragma unroll
                 for (int j = 0; j < MC; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf[j], rf[i], acc[i][j], 0, 0, 0);
-        }
-        if (MODE == MODE_UPD && tile_c == 0 && tid < TR) {
-            // R tile of the update is dZ as [sample][unit]: column tid summed over the slice's samples
+                    cf[j] = CTRANS ? frag_trans<TC>(Cs, (wc * MC + j) * 32, kk, lane)
+                                   : frag_direct(Cs, (wc * MC + j) * 32, kk, lane);
+#pragma unroll
+                for (int i = 0; i < MR; ++i)
+                    rf[i] = RTRANS ? frag_trans<TR>(Rs, (wr * MR + i) * 32, kk, lane)
+                                   : frag_direct(Rs, (wr * MR + i) * 32, kk, lane);
+#pragma unroll
+                for (int i = 0; i < MR; ++i)
+#pragma unroll
+                    for (int j = 0; j < MC; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf[j], rf[i], acc[i][j], 0, 0, 0);
+            }
+            if (MODE == MODE_UPD && tile_c == 0 && tid < TR) {
+                // R tile of the update is dZ as [sample][unit]: column tid summed over the slice's samples
 #pragma unroll 8
-            for (int k = 0; k < BK; ++k) bias_sum += bf16_to_f32(Rs[k * tpitch(TR) + tid]);
+                for (int k = 0; k < BK; ++k) bias_sum += bf16_to_f32(Rs[k * tpitch(TR) + tid]);
+            }
+            __syncthreads();
         }
-        __syncthreads();
     }
 
     // ---- epilogue: lane owns, per block, row r = l%32 and columns 8q + 4(l/32) + 0..3, q = 0..3
@@ -346,18 +358,46 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(Args a) {
     }
 }
 
-template <int MODE, int TR, int TC, int WR, int WC, bool RT, bool CT>
+template <int MODE, int TR, int TC, int WR, int WC, bool RT, bool CT, int S>
 hipError_t launch(Args a, int P, hipStream_t st) {
     a.tiles_c = (a.nC + TC - 1) / TC;
     a.tiles_r = (a.nR + TR - 1) / TR;
     a.total_wg = a.tiles_c * a.tiles_r * P;
     a.chunk = (a.total_wg + 7) / 8;
     dim3 grid(8 * a.chunk);
-    hipLaunchKernelGGL((gemm_bf16_kernel<MODE, TR, TC, WR, WC, RT, CT>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((gemm_bf16_kernel<MODE, TR, TC, WR, WC, RT, CT, S>), grid, dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
 int round8(int x) { return (x + 7) / 8 * 8; }
+
+// Tile shapes a launch can use: rows x columns of the output tile (4 wavefronts each).
+enum { T128x128 = 0, T128x64 = 1, T64x128 = 2, T64x64 = 3 };
+
+// Rows of the output beyond one tile re-read the column operand (the weights in forward and
+// backward-data), so the row tile covers the batch when it can; the column tile is then narrowed
+// until the launch has enough workgroups to occupy the 256 compute units several times over.
+int pick_tile(int nR, int nC, int P) {
+    const int tr = nR <= 64 ? 64 : 128;
+    const long wg128 = (long)((nR + tr - 1) / tr) * ((nC + 127) / 128) * P;
+    const bool narrow = wg128 < 1024 && nC > 64;
+    if (tr == 128) return narrow ? T128x64 : T128x128;
+    return narrow ? T64x64 : T64x128;
+}
+
+#ifndef KAVG_STAGES
+#define KAVG_STAGES 2
+#endif
+
+template <int MODE, bool RT, bool CT>
+hipError_t launch_tiled(const Args& a, int P, int tile, hipStream_t st) {
+    switch (tile) {
+        case T128x128: return launch<MODE, 128, 128, 2, 2, RT, CT, KAVG_STAGES>(a, P, st);
+        case T128x64:  return launch<MODE, 128, 64, 2, 2, RT, CT, KAVG_STAGES>(a, P, st);
+        case T64x128:  return launch<MODE, 64, 128, 2, 2, RT, CT, KAVG_STAGES>(a, P, st);
+        default:       return launch<MODE, 64, 64, 2, 2, RT, CT, KAVG_STAGES>(a, P, st);
+    }
+}
 
 }  // namespace
 
@@ -368,8 +408,7 @@ hipError_t bf16_forward(const LayerCall& c, hipStream_t st) {
     a.nR = c.B; a.nC = c.d_out; a.nK = c.d_in;
     a.bias = c.b; a.bias_lstride = c.w_stride;
     a.out = c.out; a.out_lstride = c.out_stride; a.ld_out = c.ld_out; a.relu = c.relu;
-    if (c.B <= 64) return launch<MODE_FWD, 64, 128, 2, 2, false, false>(a, c.P, st);
-    return launch<MODE_FWD, 128, 128, 2, 2, false, false>(a, c.P, st);
+    return launch_tiled<MODE_FWD, false, false>(a, c.P, KAVG_TILE_OVERRIDE(pick_tile(a.nR, a.nC, c.P)), st);
 }
 
 hipError_t bf16_backward_data(const LayerCall& c, hipStream_t st) {
@@ -379,8 +418,7 @@ hipError_t bf16_backward_data(const LayerCall& c, hipStream_t st) {
     a.nR = c.B; a.nC = c.d_in; a.nK = c.d_out;
     a.act_prev = (const uint16_t*)c.in; a.act_lstride = c.in_stride; a.ld_act = c.ld_in;
     a.out = c.dz_prev; a.out_lstride = c.dz_prev_stride; a.ld_out = c.ld_in;
-    if (c.B <= 64) return launch<MODE_BWD, 64, 128, 2, 2, false, true>(a, c.P, st);
-    return launch<MODE_BWD, 128, 128, 2, 2, false, true>(a, c.P, st);
+    return launch_tiled<MODE_BWD, false, true>(a, c.P, KAVG_TILE_OVERRIDE(pick_tile(a.nR, a.nC, c.P)), st);
 }
 
 hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
@@ -390,7 +428,7 @@ hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     a.nR = c.d_out; a.nC = c.d_in; a.nK = c.B;
     a.w = c.w; a.w_lstride = c.w_stride; a.ws = c.ws; a.ws_lstride = c.ws_stride; a.b = c.b;
     a.lr = c.lr;
-    return launch<MODE_UPD, 128, 128, 2, 2, true, true>(a, c.P, st);
+    return launch<MODE_UPD, 128, 128, 2, 2, true, true, 1>(a, c.P, st);
 }
 
 }  // namespace kavg
