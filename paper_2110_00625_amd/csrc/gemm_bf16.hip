@@ -50,9 +50,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int BK = 64;          // contraction slice held in LDS
-constexpr int BKP = BK + 8;     // padded LDS row (bf16 elements): 144 bytes, keeps 16-byte alignment
-
 enum { MODE_FWD = 0, MODE_BWD = 1, MODE_UPD = 2 };
 
 struct Operand {
@@ -93,66 +90,80 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t h) {
 }
 
 // ---- staging: global -> registers -> LDS ------------------------------------
-// Every thread moves X/32 pieces of 16 bytes per operand and slice.
-template <int X> struct StageRegs { u32x4 v[X / 32]; };
+// A slice is BK along the contraction.  Every thread of the NT-thread workgroup moves
+// X*BK/8/NT pieces of 16 bytes per operand and slice.
+template <int N> struct StageRegs { u32x4 v[N]; };
 
+constexpr int dpitch(int BK) { return BK + 8; }    // [x][k] tile: row of BK bf16 plus 16 bytes
 constexpr int tpitch(int X) { return X + 32; }     // [k][x] tile: row of X bf16 plus 64 bytes
 
-// direct operand: piece e covers memory row x0 + e/8, k0 + 8*(e%8) .. +7
-template <int X>
-__device__ __forceinline__ void load_direct(StageRegs<X>& g, const Operand& o, const uint16_t* base,
-                                            const int32_t* gather, int x0, int k0, int tid) {
+// Direct operand: piece e covers memory row x0 + e/(BK/8), k0 + 8*(e%(BK/8)) .. +7.  The row a
+// piece reads does not change from slice to slice, so its address (and gather lookup) is formed once.
+template <int X, int BK, int NT>
+struct DirectLoader {
+    static constexpr int N = X * BK / 8 / NT;
+    const uint16_t* rowp[N];     // null: row outside the operand
+    int kc[N];
+    __device__ __forceinline__ void init(const Operand& o, const uint16_t* base, const int32_t* gather, int x0, int tid) {
 #pragma unroll
-    for (int i = 0; i < X / 32; ++i) {
-        const int e = tid + 256 * i;
-        const int x = x0 + (e >> 3), k = k0 + (e & 7) * 8;
-        u32x4 val = {0u, 0u, 0u, 0u};
-        if (x < o.n_rows && k < o.n_cont) {
-            const long row = gather ? (long)gather[x] : (long)x;
-            val = *(const u32x4*)(base + row * o.ld + k);
+        for (int i = 0; i < N; ++i) {
+            const int e = tid + NT * i;
+            const int x = x0 + e / (BK / 8);
+            kc[i] = (e % (BK / 8)) * 8;
+            rowp[i] = nullptr;
+            if (x < o.n_rows) rowp[i] = base + (gather ? (long)gather[x] : (long)x) * o.ld + kc[i];
         }
-        g.v[i] = val;
     }
-}
-
-template <int X>
-__device__ __forceinline__ void store_direct(const StageRegs<X>& g, uint16_t* lds, int tid) {
+    __device__ __forceinline__ void load(StageRegs<N>& g, const Operand& o, int k0) const {
 #pragma unroll
-    for (int i = 0; i < X / 32; ++i) {
-        const int e = tid + 256 * i;
-        *(u32x4*)(lds + (e >> 3) * BKP + (e & 7) * 8) = g.v[i];
-    }
-}
-
-// transposed operand: piece e covers memory row k0 + e/(X/8), columns x0 + 8*(e%(X/8)) .. +7
-template <int X>
-__device__ __forceinline__ void load_trans(StageRegs<X>& g, const Operand& o, const uint16_t* base,
-                                           const int32_t* gather, int x0, int k0, int tid) {
-#pragma unroll
-    for (int i = 0; i < X / 32; ++i) {
-        const int e = tid + 256 * i;
-        const int k = k0 + e / (X / 8), x = x0 + (e % (X / 8)) * 8;
-        u32x4 val = {0u, 0u, 0u, 0u};
-        if (k < o.n_rows && x < o.n_cont) {
-            const long row = gather ? (long)gather[k] : (long)k;
-            val = *(const u32x4*)(base + row * o.ld + x);
+        for (int i = 0; i < N; ++i) {
+            u32x4 val = {0u, 0u, 0u, 0u};
+            if (rowp[i] && k0 + kc[i] < o.n_cont) val = *(const u32x4*)(rowp[i] + k0);
+            g.v[i] = val;
         }
-        g.v[i] = val;
     }
-}
-
-template <int X>
-__device__ __forceinline__ void store_trans(const StageRegs<X>& g, uint16_t* lds, int tid) {
+    __device__ __forceinline__ void store(const StageRegs<N>& g, uint16_t* lds, int tid) const {
 #pragma unroll
-    for (int i = 0; i < X / 32; ++i) {
-        const int e = tid + 256 * i;
-        *(u32x4*)(lds + (e / (X / 8)) * tpitch(X) + (e % (X / 8)) * 8) = g.v[i];
+        for (int i = 0; i < N; ++i) {
+            const int e = tid + NT * i;
+            *(u32x4*)(lds + (e / (BK / 8)) * dpitch(BK) + (e % (BK / 8)) * 8) = g.v[i];
+        }
     }
-}
+};
 
-// MFMA fragment (lane l: index l%32 of the 32-block, k = 8*(l/32) .. +7 of the 16-slab)
+// Transposed operand: piece e covers memory row k0 + e/(X/8), columns x0 + 8*(e%(X/8)) .. +7.
+template <int X, int BK, int NT>
+struct TransLoader {
+    static constexpr int N = X * BK / 8 / NT;
+    const uint16_t* colp;        // base + this thread's column offset; null: columns outside the operand
+    const int32_t* gather;
+    __device__ __forceinline__ void init(const Operand& o, const uint16_t* base, const int32_t* g, int x0, int tid) {
+        const int x = x0 + (tid % (X / 8)) * 8;      // NT is a multiple of X/8: same column for every piece
+        colp = x < o.n_cont ? base + x : nullptr;
+        gather = g;
+    }
+    __device__ __forceinline__ void load(StageRegs<N>& g, const Operand& o, int k0, int tid) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int k = k0 + (tid + NT * i) / (X / 8);
+            u32x4 val = {0u, 0u, 0u, 0u};
+            if (colp && k < o.n_rows) val = *(const u32x4*)(colp + (gather ? (long)gather[k] : (long)k) * o.ld);
+            g.v[i] = val;
+        }
+    }
+    __device__ __forceinline__ void store(const StageRegs<N>& g, uint16_t* lds, int tid) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int e = tid + NT * i;
+            *(u32x4*)(lds + (e / (X / 8)) * tpitch(X) + (e % (X / 8)) * 8) = g.v[i];
+        }
+    }
+};
+
+// MFMA fragment (lane l: index l%32 of the 32-block, k = 8*(l/32) .. +7 of the 16-slab kk)
+template <int BK>
 __device__ __forceinline__ bf16x8 frag_direct(const uint16_t* tile, int block_row0, int kk, int lane) {
-    return *(const bf16x8*)(tile + (block_row0 + (lane & 31)) * BKP + kk * 16 + (lane >> 5) * 8);
+    return *(const bf16x8*)(tile + (block_row0 + (lane & 31)) * dpitch(BK) + kk * 16 + (lane >> 5) * 8);
 }
 
 // Same fragment out of a [k][x] tile with two transpose reads.  In its 16-lane group, lane t = 4a + b
@@ -171,27 +182,34 @@ __device__ __forceinline__ bf16x8 frag_trans(const uint16_t* tile, int block_x0,
 }
 
 // ---- the kernel ----------------------------------------------------------------
-// TR x TC output tile, 4 wavefronts arranged WR x WC, each owning MR x MC MFMA blocks of 32x32.
-// S = slices kept in flight in registers ahead of the one being multiplied.
-template <int MODE, int TR, int TC, int WR, int WC, bool RTRANS, bool CTRANS, int S>
-__global__ void __launch_bounds__(256) gemm_bf16_kernel(Args a) {
-    static_assert(WR * WC == 4, "four wavefronts per workgroup");
+// TR x TC output tile; WR x WC x WK wavefronts: WR x WC of them tile the output, each owning MR x MC
+// MFMA blocks of 32x32, and WK groups of those split every slice along k (their partial tiles are
+// summed through LDS at the end, in fixed order).  BK = slice length.  S = slices kept in flight in
+// registers ahead of the one being multiplied.
+template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RTRANS, bool CTRANS, int S>
+__global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
+    constexpr int NW = WR * WC * WK, NT = 64 * NW;
     constexpr int MR = TR / (32 * WR), MC = TC / (32 * WC);
     static_assert(MR >= 1 && MC >= 1, "tile too small for the wave grid");
-    // update epilogue: each wavefront turns one 32-row block of its accumulators into rows in LDS
+    static_assert((BK / 16) % WK == 0, "slice must split evenly over the k groups");
+    static_assert(MODE != MODE_UPD || (WK == 1 && NW == 4), "the update epilogue assumes 4 wavefronts, no k split");
+    static_assert(NT % (TR / 8) == 0 && NT % (TC / 8) == 0, "loader column mapping");
     constexpr int WTC = MC * 32;                 // columns of a wavefront's tile
-    constexpr int SPITCH = WTC + 4;              // fp32 staging row, padded
-    constexpr int R_ELEMS = RTRANS ? BK * tpitch(TR) : TR * BKP;
-    constexpr int C_ELEMS = CTRANS ? BK * tpitch(TC) : TC * BKP;
+    constexpr int SPITCH = WTC + 4;              // update epilogue: fp32 staging row, padded
+    constexpr int R_ELEMS = RTRANS ? BK * tpitch(TR) : TR * dpitch(BK);
+    constexpr int C_ELEMS = CTRANS ? BK * tpitch(TC) : TC * dpitch(BK);
     constexpr int OPER_BYTES = (R_ELEMS + C_ELEMS) * 2;
     constexpr int STAGE_BYTES = MODE == MODE_UPD ? 4 * 32 * SPITCH * 4 : 0;
-    constexpr int SMEM_BYTES = OPER_BYTES > STAGE_BYTES ? OPER_BYTES : STAGE_BYTES;
+    constexpr int KRED_BYTES = (WK - 1) * WR * WC * MR * MC * 16 * 64 * 4;
+    constexpr int SMEM1 = OPER_BYTES > STAGE_BYTES ? OPER_BYTES : STAGE_BYTES;
+    constexpr int SMEM_BYTES = SMEM1 > KRED_BYTES ? SMEM1 : KRED_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
     uint16_t* Rs = (uint16_t*)smem;
     uint16_t* Cs = Rs + R_ELEMS;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wr = wave / WC, wc = wave % WC;
+    const int wk = wave / (WR * WC), wrc = wave % (WR * WC);
+    const int wr = wrc / WC, wc = wrc % WC;
     // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2) in launch order, so
     // workgroup g runs on XCD g%8.  Give every XCD one contiguous range of the logical order
     // (learner, row tile, column tile): the tiles of a learner then share that learner's operands
@@ -216,17 +234,21 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(Args a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    StageRegs<TR> rg[S];
-    StageRegs<TC> cg[S];
+    DirectLoader<TR, BK, NT> rdl; TransLoader<TR, BK, NT> rtl;
+    DirectLoader<TC, BK, NT> cdl; TransLoader<TC, BK, NT> ctl;
+    if (RTRANS) rtl.init(a.R, Rbase, Rg, r0, tid); else rdl.init(a.R, Rbase, Rg, r0, tid);
+    if (CTRANS) ctl.init(a.C, Cbase, Cg, c0, tid); else cdl.init(a.C, Cbase, Cg, c0, tid);
+    StageRegs<TR * BK / 8 / NT> rg[S];
+    StageRegs<TC * BK / 8 / NT> cg[S];
     float bias_sum = 0.f;                       // update: column sum of dZ for row r0 + tid
 
-    auto fetch = [&](StageRegs<TR>& r, StageRegs<TC>& c, int k0) {
-        if (RTRANS) load_trans<TR>(r, a.R, Rbase, Rg, r0, k0, tid); else load_direct<TR>(r, a.R, Rbase, Rg, r0, k0, tid);
-        if (CTRANS) load_trans<TC>(c, a.C, Cbase, Cg, c0, k0, tid); else load_direct<TC>(c, a.C, Cbase, Cg, c0, k0, tid);
+    auto fetch = [&](StageRegs<TR * BK / 8 / NT>& r, StageRegs<TC * BK / 8 / NT>& c, int k0) {
+        if (RTRANS) rtl.load(r, a.R, k0, tid); else rdl.load(r, a.R, k0);
+        if (CTRANS) ctl.load(c, a.C, k0, tid); else cdl.load(c, a.C, k0);
     };
-    auto stash = [&](const StageRegs<TR>& r, const StageRegs<TC>& c) {
-        if (RTRANS) store_trans<TR>(r, Rs, tid); else store_direct<TR>(r, Rs, tid);
-        if (CTRANS) store_trans<TC>(c, Cs, tid); else store_direct<TC>(c, Cs, tid);
+    auto stash = [&](const StageRegs<TR * BK / 8 / NT>& r, const StageRegs<TC * BK / 8 / NT>& c) {
+        if (RTRANS) rtl.store(r, Rs, tid); else rdl.store(r, Rs, tid);
+        if (CTRANS) ctl.store(c, Cs, tid); else cdl.store(c, Cs, tid);
     };
 
 #pragma unroll
@@ -241,16 +263,17 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(Args a) {
             __syncthreads();
             if (k0 + S * BK < a.nK) fetch(rg[s], cg[s], k0 + S * BK);   // S slices ahead, in flight during the MFMAs
 #pragma unroll
-            for (int kk = 0; kk < BK / 16; ++kk) {
+            for (int kq = 0; kq < BK / 16 / WK; ++kq) {
+                const int kk = wk * (BK / 16 / WK) + kq;
                 bf16x8 cf[MC], rf[MR];
 #pragma unroll
                 for (int j = 0; j < MC; ++j)
                     cf[j] = CTRANS ? frag_trans<TC>(Cs, (wc * MC + j) * 32, kk, lane)
-                                   : frag_direct(Cs, (wc * MC + j) * 32, kk, lane);
+                                   : frag_direct<BK>(Cs, (wc * MC + j) * 32, kk, lane);
 #pragma unroll
                 for (int i = 0; i < MR; ++i)
                     rf[i] = RTRANS ? frag_trans<TR>(Rs, (wr * MR + i) * 32, kk, lane)
-                                   : frag_direct(Rs, (wr * MR + i) * 32, kk, lane);
+                                   : frag_direct<BK>(Rs, (wr * MR + i) * 32, kk, lane);
 #pragma unroll
                 for (int i = 0; i < MR; ++i)
 #pragma unroll
@@ -264,6 +287,34 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(Args a) {
             }
             __syncthreads();
         }
+    }
+
+    if (WK > 1) {
+        // sum the k groups' partial tiles into group 0, group by group (fixed order)
+        float* red = (float*)smem;
+#pragma unroll
+        for (int g = 1; g < WK; ++g) {
+            if (wk == g) {
+#pragma unroll
+                for (int i = 0; i < MR; ++i)
+#pragma unroll
+                    for (int j = 0; j < MC; ++j)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            red[(((g - 1) * WR * WC + wrc) * MR * MC * 16 + (i * MC + j) * 16 + e) * 64 + lane] = acc[i][j][e];
+            }
+        }
+        __syncthreads();
+        if (wk != 0) return;
+#pragma unroll
+        for (int g = 1; g < WK; ++g)
+#pragma unroll
+            for (int i = 0; i < MR; ++i)
+#pragma unroll
+                for (int j = 0; j < MC; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        acc[i][j][e] += red[(((g - 1) * WR * WC + wrc) * MR * MC * 16 + (i * MC + j) * 16 + e) * 64 + lane];
     }
 
     // ---- epilogue: lane owns, per block, row r = l%32 and columns 8q + 4(l/32) + 0..3, q = 0..3
@@ -358,44 +409,44 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(Args a) {
     }
 }
 
-template <int MODE, int TR, int TC, int WR, int WC, bool RT, bool CT, int S>
+template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RT, bool CT, int S>
 hipError_t launch(Args a, int P, hipStream_t st) {
     a.tiles_c = (a.nC + TC - 1) / TC;
     a.tiles_r = (a.nR + TR - 1) / TR;
     a.total_wg = a.tiles_c * a.tiles_r * P;
     a.chunk = (a.total_wg + 7) / 8;
     dim3 grid(8 * a.chunk);
-    hipLaunchKernelGGL((gemm_bf16_kernel<MODE, TR, TC, WR, WC, RT, CT, S>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, S>), grid, dim3(64 * WR * WC * WK),
+                       0, st, a);
     return hipGetLastError();
 }
 
 int round8(int x) { return (x + 7) / 8 * 8; }
 
-// Tile shapes a launch can use: rows x columns of the output tile (4 wavefronts each).
-enum { T128x128 = 0, T128x64 = 1, T64x128 = 2, T64x64 = 3 };
+// Launch shapes: rows x columns of the output tile (_K2: eight wavefronts, two k groups, slices of 128).
+enum { T128x128 = 0, T128x64 = 1, T64x128 = 2, T64x64_K2 = 3 };
 
-// Rows of the output beyond one tile re-read the column operand (the weights in forward and
-// backward-data), so the row tile covers the batch when it can; the column tile is then narrowed
-// until the launch has enough workgroups to occupy the 256 compute units several times over.
-int pick_tile(int nR, int nC, int P) {
-    const int tr = nR <= 64 ? 64 : 128;
-    const long wg128 = (long)((nR + tr - 1) / tr) * ((nC + 127) / 128) * P;
-    const bool narrow = wg128 < 1024 && nC > 64;
-    if (tr == 128) return narrow ? T128x64 : T128x128;
-    return narrow ? T64x64 : T64x128;
+// Measured on MI355X over the workload shapes (batch 64..256, widths 1024..4096, 8..32 learners):
+// with >= 512 tiles of 128x128 the launch fills the chip with the tile that reads LDS least per
+// flop; smaller problems are LDS- and barrier-bound per workgroup, and the 64x64 tile with two k
+// groups (most wavefronts per compute unit, half as many barriers per k) wins.
+int pick_tile(int mode, int nR, int nC, int P) {
+    const long tiles128 = (long)((nR + 127) / 128) * ((nC + 127) / 128) * P;
+    if (mode == MODE_FWD) {
+        if (nR <= 64) return (long)((nC + 127) / 128) * P >= 512 ? T64x128 : T64x64_K2;
+        return tiles128 >= 512 ? T128x128 : T64x64_K2;
+    }
+    if (nR <= 64) return T64x64_K2;
+    return tiles128 >= 256 ? T128x64 : T64x64_K2;
 }
-
-#ifndef KAVG_STAGES
-#define KAVG_STAGES 2
-#endif
 
 template <int MODE, bool RT, bool CT>
 hipError_t launch_tiled(const Args& a, int P, int tile, hipStream_t st) {
     switch (tile) {
-        case T128x128: return launch<MODE, 128, 128, 2, 2, RT, CT, KAVG_STAGES>(a, P, st);
-        case T128x64:  return launch<MODE, 128, 64, 2, 2, RT, CT, KAVG_STAGES>(a, P, st);
-        case T64x128:  return launch<MODE, 64, 128, 2, 2, RT, CT, KAVG_STAGES>(a, P, st);
-        default:       return launch<MODE, 64, 64, 2, 2, RT, CT, KAVG_STAGES>(a, P, st);
+        case T128x128: return launch<MODE, 128, 128, 2, 2, 1, 64, RT, CT, 1>(a, P, st);
+        case T128x64:  return launch<MODE, 128, 64, 2, 2, 1, 64, RT, CT, 1>(a, P, st);
+        case T64x128:  return launch<MODE, 64, 128, 2, 2, 1, 64, RT, CT, 1>(a, P, st);
+        default:       return launch<MODE, 64, 64, 2, 2, 2, 128, RT, CT, 1>(a, P, st);
     }
 }
 
@@ -408,7 +459,7 @@ hipError_t bf16_forward(const LayerCall& c, hipStream_t st) {
     a.nR = c.B; a.nC = c.d_out; a.nK = c.d_in;
     a.bias = c.b; a.bias_lstride = c.w_stride;
     a.out = c.out; a.out_lstride = c.out_stride; a.ld_out = c.ld_out; a.relu = c.relu;
-    return launch_tiled<MODE_FWD, false, false>(a, c.P, KAVG_TILE_OVERRIDE(pick_tile(a.nR, a.nC, c.P)), st);
+    return launch_tiled<MODE_FWD, false, false>(a, c.P, KAVG_TILE_OVERRIDE(pick_tile(MODE_FWD, a.nR, a.nC, c.P)), st);
 }
 
 hipError_t bf16_backward_data(const LayerCall& c, hipStream_t st) {
@@ -418,7 +469,7 @@ hipError_t bf16_backward_data(const LayerCall& c, hipStream_t st) {
     a.nR = c.B; a.nC = c.d_in; a.nK = c.d_out;
     a.act_prev = (const uint16_t*)c.in; a.act_lstride = c.in_stride; a.ld_act = c.ld_in;
     a.out = c.dz_prev; a.out_lstride = c.dz_prev_stride; a.ld_out = c.ld_in;
-    return launch_tiled<MODE_BWD, false, true>(a, c.P, KAVG_TILE_OVERRIDE(pick_tile(a.nR, a.nC, c.P)), st);
+    return launch_tiled<MODE_BWD, false, true>(a, c.P, KAVG_TILE_OVERRIDE(pick_tile(MODE_BWD, a.nR, a.nC, c.P)), st);
 }
 
 hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
@@ -428,7 +479,7 @@ hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     a.nR = c.d_out; a.nC = c.d_in; a.nK = c.B;
     a.w = c.w; a.w_lstride = c.w_stride; a.ws = c.ws; a.ws_lstride = c.ws_stride; a.b = c.b;
     a.lr = c.lr;
-    return launch<MODE_UPD, 128, 128, 2, 2, true, true, 1>(a, c.P, st);
+    return launch<MODE_UPD, 128, 128, 2, 2, 1, 64, true, true, 1>(a, c.P, st);
 }
 
 }  // namespace kavg
