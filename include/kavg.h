@@ -134,12 +134,14 @@ int kavg_losses(kavg_ctx* ctx, float* out_host);
 int kavg_indices(kavg_ctx* ctx, int32_t* out_host);
 
 /* Measurement aid for callers that report per-kernel time (not part of the
- * method): while a class's bit is set in class_mask, every launch of that class
- * is bracketed by a HIP event pair on the context's stream.  kavg_profile waits
- * for the stream, clears the totals and installs the mask (0 = off);
- * kavg_profile_read waits for the stream and returns, per class, the summed
- * elapsed milliseconds and the number of launches since then
- * (arrays of KAVG_NCLASS entries, host). */
+ * method): while a class's bit is set in class_mask, one launch in `every` of
+ * that class (the first, the every+1-th, ...) is bracketed by a HIP event pair
+ * on the context's stream; an event costs a few microseconds of stream time, so
+ * a sparse sample keeps the timed region close to an unobserved one.
+ * kavg_profile waits for the stream, clears the totals and installs the mask
+ * (0 = off); kavg_profile_read waits for the stream and returns, per class, the
+ * summed elapsed milliseconds and the number of bracketed launches since then
+ * (arrays of KAVG_NCLASS entries, host).  KAVG_EINVAL: unknown class bit, every < 1. */
 #define KAVG_CLASS_INDEX    0   /* minibatch index stream / import        */
 #define KAVG_CLASS_FORWARD  1   /* per-layer forward products              */
 #define KAVG_CLASS_LOSS     2   /* softmax cross-entropy + gradient, loss mean */
@@ -147,7 +149,7 @@ int kavg_indices(kavg_ctx* ctx, int32_t* out_host);
 #define KAVG_CLASS_UPDATE   4   /* per-layer weight gradient + SGD update  */
 #define KAVG_CLASS_META     5   /* fused meta step                         */
 #define KAVG_NCLASS         6
-int kavg_profile(kavg_ctx* ctx, unsigned class_mask);
+int kavg_profile(kavg_ctx* ctx, unsigned class_mask, unsigned every);
 int kavg_profile_read(kavg_ctx* ctx, double* ms_out, long long* launches_out);
 
 uint64_t    kavg_round(const kavg_ctx* ctx);

@@ -251,6 +251,25 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
         if (CTRANS) ctl.store(c, Cs, tid); else cdl.store(c, Cs, tid);
     };
 
+    // Update: the fp32 master tile is independent of the product, so its loads go out first and
+    // are in flight during the whole contraction (the kernel is bound by this stream, not by MFMAs).
+    constexpr int F4_PER_ROW = WTC / 4;
+    constexpr int ROWS_PER_IT = 64 / F4_PER_ROW;
+    constexpr int ITS = 32 / ROWS_PER_IT;
+    f32x4 mst[MODE == MODE_UPD ? MR : 1][MODE == MODE_UPD ? ITS : 1];
+    if (MODE == MODE_UPD) {
+        const float* wbase = a.w + (size_t)learner * a.w_lstride;
+        const int c = c0 + wc * WTC + (lane % F4_PER_ROW) * 4;
+#pragma unroll
+        for (int i = 0; i < MR; ++i)
+#pragma unroll
+            for (int it = 0; it < ITS; ++it) {
+                const int r = r0 + (wr * MR + i) * 32 + it * ROWS_PER_IT + lane / F4_PER_ROW;
+                mst[i][it] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                if (r < a.nR && c < a.nC) mst[i][it] = __builtin_nontemporal_load((const f32x4*)(wbase + (size_t)r * a.nC + c));
+            }
+    }
+
 #pragma unroll
     for (int s = 0; s < S; ++s)
         if (s * BK < a.nK) fetch(rg[s], cg[s], s * BK);
@@ -362,9 +381,6 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
         // Update: the master tile is read and written as whole row segments.  Each wavefront passes one
         // 32-row block of its accumulators through a private LDS patch so that a lane ends up with four
         // consecutive columns of a row and 64/(WTC/4) rows are covered per access, WTC*4 contiguous bytes each.
-        constexpr int F4_PER_ROW = WTC / 4;
-        constexpr int ROWS_PER_IT = 64 / F4_PER_ROW;
-        constexpr int ITS = 32 / ROWS_PER_IT;
         float* stage = (float*)smem + wave * 32 * SPITCH;
         float* wbase = a.w + (size_t)learner * a.w_lstride;
         uint16_t* sbase = a.ws + (size_t)learner * a.ws_lstride;
@@ -373,14 +389,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
 #pragma unroll
         for (int i = 0; i < MR; ++i) {
             const int rblk = r0 + (wr * MR + i) * 32;
-            f32x4 m[ITS];
-#pragma unroll
-            for (int it = 0; it < ITS; ++it) {          // master loads go out before the LDS shuffle
-                const int r = rblk + it * ROWS_PER_IT + rr;
-                m[it] = (f32x4){0.f, 0.f, 0.f, 0.f};
-                if (r < a.nR && c < a.nC) m[it] = *(const f32x4*)(wbase + (size_t)r * a.nC + c);
-            }
-            __syncthreads();                            // previous patch contents (or operand tiles) are dead
+            if (i > 0) __syncthreads();                 // previous patch contents are dead
 #pragma unroll
             for (int j = 0; j < MC; ++j)
 #pragma unroll
@@ -394,7 +403,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                 const int r = rblk + it * ROWS_PER_IT + rr;
                 const f32x4 g = *(const f32x4*)(stage + (it * ROWS_PER_IT + rr) * SPITCH + cc);
                 if (r < a.nR && c < a.nC) {
-                    f32x4 w = m[it];
+                    f32x4 w = mst[i][it];
                     w.x -= a.lr * g.x; w.y -= a.lr * g.y; w.z -= a.lr * g.z; w.w -= a.lr * g.w;
                     *(f32x4*)(wbase + (size_t)r * a.nC + c) = w;
                     u32x2 o = {pack2(w.x, w.y), pack2(w.z, w.w)};

@@ -96,6 +96,8 @@ struct kavg_ctx {
     char err[256];
     // measurement aid: HIP event pairs around the launches of selected kernel classes
     unsigned prof_mask;
+    unsigned prof_every;                            // bracket one launch in prof_every of a class
+    unsigned long long prof_seen[KAVG_NCLASS];      // launches of the class since kavg_profile
     std::vector<hipEvent_t> prof_ev[KAVG_NCLASS];   // start/stop alternate
     size_t prof_used[KAVG_NCLASS];
     double prof_ms[KAVG_NCLASS];
@@ -161,6 +163,7 @@ struct Bracket {
     kavg_ctx* c; int cls; bool on; hipEvent_t stop;
     Bracket(kavg_ctx* ctx, int k) : c(ctx), cls(k), on(false), stop(nullptr) {
         if (!(c->prof_mask & (1u << cls))) return;
+        if ((c->prof_seen[cls]++ % c->prof_every) != 0) return;
         std::vector<hipEvent_t>& pool = c->prof_ev[cls];
         while (pool.size() < c->prof_used[cls] + 2) {
             hipEvent_t e;
@@ -252,7 +255,8 @@ int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, co
     c->t0 = 0; c->round = 0; c->have_params = false; c->have_steps = false;
     c->err[0] = 0;
     c->prof_mask = 0;
-    for (int k = 0; k < KAVG_NCLASS; ++k) { c->prof_used[k] = 0; c->prof_ms[k] = 0.0; c->prof_launches[k] = 0; }
+    c->prof_every = 1;
+    for (int k = 0; k < KAVG_NCLASS; ++k) { c->prof_used[k] = 0; c->prof_ms[k] = 0.0; c->prof_launches[k] = 0; c->prof_seen[k] = 0; }
     hipError_t e = hipMemsetAsync(c->flag(), 0, ALIGN, c->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) {
@@ -415,13 +419,15 @@ static int prof_drain(kavg_ctx* c) {
     return KAVG_OK;
 }
 
-int kavg_profile(kavg_ctx* c, unsigned class_mask) {
+int kavg_profile(kavg_ctx* c, unsigned class_mask, unsigned every) {
     if (!c) return KAVG_EINVAL;
     if (class_mask >> KAVG_NCLASS) return fail(c, KAVG_EINVAL, "unknown kernel class in mask");
+    if (every < 1) return fail(c, KAVG_EINVAL, "every must be >= 1");
     int rc = prof_drain(c);
     if (rc != KAVG_OK) return rc;
-    for (int k = 0; k < KAVG_NCLASS; ++k) { c->prof_ms[k] = 0.0; c->prof_launches[k] = 0; }
+    for (int k = 0; k < KAVG_NCLASS; ++k) { c->prof_ms[k] = 0.0; c->prof_launches[k] = 0; c->prof_seen[k] = 0; }
     c->prof_mask = class_mask;
+    c->prof_every = every;
     return KAVG_OK;
 }
 

@@ -68,7 +68,7 @@ def load_library():
         "kavg_losses": [c_vp, c_vp],
         "kavg_indices": [c_vp, c_vp],
         "kavg_destroy": [c_vp],
-        "kavg_profile": [c_vp, ctypes.c_uint],
+        "kavg_profile": [c_vp, ctypes.c_uint, ctypes.c_uint],
         "kavg_profile_read": [c_vp, c_vp, c_vp],
         "kavg_meta_update_flat": [c_vp, c_vp, c_vp, c_sz, c_vp, c_sz, c_int, c_sz, c_f, c_vp],
     }.items():
@@ -207,12 +207,12 @@ class MAvg:
         _check(self.lib, self.ctx, self.lib.kavg_indices(self.ctx, out.ctypes.data))
         return out
 
-    def profile(self, classes):
-        """Bracket the launches of the named kernel classes with HIP events (() = off)."""
+    def profile(self, classes, every=1):
+        """Bracket one launch in `every` of the named kernel classes with HIP events (() = off)."""
         mask = 0
         for name in classes:
             mask |= 1 << CLASS_NAMES.index(name)
-        _check(self.lib, self.ctx, self.lib.kavg_profile(self.ctx, mask))
+        _check(self.lib, self.ctx, self.lib.kavg_profile(self.ctx, mask, int(every)))
 
     def profile_read(self):
         """{class: (total ms, launches)} since the last profile() call."""
