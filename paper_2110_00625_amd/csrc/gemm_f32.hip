@@ -1,11 +1,11 @@
 // fp32 path of the learner step (KAVG_FP32): forward, backward-data and the
-// fused weight-gradient + SGD update, batched over learners (grid.z).
+// fused weight-gradient + SGD update, batched over learners.
 //
 // One generic LDS-tiled kernel computes   O[r][c] = sum_k R(r,k) * Cm(c,k)
 // for operands given by (row stride, contraction stride, optional row gather),
 // with three epilogues.  Products and sums are plain fp32 FMAs (no reduced
 // precision matrix path), contraction in ascending k inside each thread, so
-// results are deterministic and independent of the grid.
+// results are deterministic and independent of timing.
 //
 //   forward        r = sample, c = output unit, k = input unit
 //                  O = act(A_{l-1} W_l^T + b_l)
@@ -14,6 +14,12 @@
 //   update         r = output unit, c = input unit, k = sample
 //                  W_l <- W_l - lr * dZ_l^T A_{l-1};  b_l <- b_l - lr * colsum(dZ_l)
 //                  (the learner update of Algorithm 1; 1/B already sits in dZ_L)
+//
+// The fp32 workloads are small (a few output tiles per learner, long
+// contractions), so the forward pass may split the contraction over several
+// workgroups: each writes its partial tile to a scratch buffer and a second
+// small kernel adds the partials in ascending split order, then applies bias
+// and ReLU.  The number of splits depends only on the shapes.
 #include "kavg_internal.h"
 
 namespace kavg {
@@ -21,10 +27,11 @@ namespace kavg {
 namespace {
 
 constexpr int TILE = 64;   // output tile is TILE x TILE
-constexpr int BK = 16;     // contraction slice
+constexpr int BK = 32;     // contraction slice
 constexpr int PADW = TILE + 4;
+constexpr int NPER = TILE * BK / 256;   // elements of a slice each thread moves per operand
 
-enum { EPI_FWD = 0, EPI_BWD = 1, EPI_UPD = 2 };
+enum { EPI_FWD = 0, EPI_BWD = 1, EPI_UPD = 2, EPI_PARTIAL = 3 };
 
 struct Operand {
     const float* base;      // learner 0
@@ -39,9 +46,11 @@ struct Operand {
 struct Args {
     Operand R, C;
     int nR, nC, nK;
+    int k_chunk;            // contraction range of one split (multiple of BK); nK when not split
     // epilogue
-    float* out;  size_t out_stride;  int ld_out;       // FWD/BWD output, UPD: master weights
-    const float* bias; size_t bias_stride;             // FWD: bias; UPD: unused
+    float* out;  size_t out_stride;  int ld_out;       // FWD/BWD output, UPD: master weights, PARTIAL: scratch
+    size_t split_stride;                               // PARTIAL: elements between splits
+    const float* bias; size_t bias_stride;             // FWD: bias
     float* bias_rw;                                    // UPD: bias to update (stride = bias_stride)
     const float* mask; size_t mask_stride; int ld_mask;// BWD: previous activations
     const float* dz; size_t dz_stride; int ld_dz;      // UPD: dZ for the bias gradient [B][ld_dz]
@@ -49,14 +58,37 @@ struct Args {
     float lr;
 };
 
-__device__ __forceinline__ float fetch(const Operand& o, int learner, int x, int k) {
-    const float* p = o.base + (size_t)learner * o.learner_stride;
-    if (o.gather) {
-        const int32_t* g = o.gather + (long)learner * o.gather_stride;
-        if (o.gather_on_k) return p[(long)g[k] * o.ld_k + (long)x * o.ld_x];
-        return p[(long)g[x] * o.ld_x + (long)k * o.ld_k];
+// Where thread `tid` finds its NPER elements of a slice: element i is (x, k) with the memory-
+// contiguous index running fastest over the threads.
+struct Mover {
+    const float* p[NPER];   // address for k = 0 (null: x outside the operand); unused for k-gathered operands
+    int x[NPER], k[NPER];
+};
+
+__device__ __forceinline__ void mover_init(Mover& m, const Operand& o, int learner, int x0, int nX, int tid) {
+    const float* base = o.base + (size_t)learner * o.learner_stride;
+    const int32_t* g = o.gather ? o.gather + (long)learner * o.gather_stride : nullptr;
+    const bool kfast = (o.ld_k == 1 && !(g && o.gather_on_k));
+#pragma unroll
+    for (int i = 0; i < NPER; ++i) {
+        const int e = tid + 256 * i;
+        if (kfast) { m.x[i] = e / BK; m.k[i] = e % BK; } else { m.x[i] = e % TILE; m.k[i] = e / TILE; }
+        const int x = x0 + m.x[i];
+        m.p[i] = nullptr;
+        if (x < nX) {
+            const long row = (g && !o.gather_on_k) ? (long)g[x] : (long)x;
+            m.p[i] = base + row * o.ld_x;
+        }
     }
-    return p[(long)x * o.ld_x + (long)k * o.ld_k];
+}
+
+__device__ __forceinline__ float mover_load(const Mover& m, const Operand& o, int learner, int i, int k, int nK) {
+    if (!m.p[i] || k >= nK) return 0.f;
+    if (o.gather && o.gather_on_k) {
+        const int32_t* g = o.gather + (long)learner * o.gather_stride;
+        return m.p[i][(long)g[k] * o.ld_k];
+    }
+    return m.p[i][(long)k * o.ld_k];
 }
 
 template <int EPI>
@@ -64,28 +96,38 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(Args a) {
     __shared__ float Rs[BK][PADW];
     __shared__ float Cs[BK][PADW];
     const int tid = threadIdx.x;
-    const int learner = blockIdx.z;
+    const int split = blockIdx.z % ((a.nK + a.k_chunk - 1) / a.k_chunk);
+    const int learner = blockIdx.z / ((a.nK + a.k_chunk - 1) / a.k_chunk);
     const int r0 = blockIdx.y * TILE, c0 = blockIdx.x * TILE;
     const int tx = tid & 15, ty = tid >> 4;
-    const bool r_kfast = (a.R.ld_k == 1 && !(a.R.gather && a.R.gather_on_k));
-    const bool c_kfast = (a.C.ld_k == 1 && !(a.C.gather && a.C.gather_on_k));
+    const int k_begin = split * a.k_chunk;
+    const int k_end = k_begin + a.k_chunk < a.nK ? k_begin + a.k_chunk : a.nK;
+
+    Mover mr, mc;
+    mover_init(mr, a.R, learner, r0, a.nR, tid);
+    mover_init(mc, a.C, learner, c0, a.nC, tid);
 
     float acc[4][4] = {};
-    for (int k0 = 0; k0 < a.nK; k0 += BK) {
+    float rv_next[NPER], cv_next[NPER];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int e = tid + 256 * i;
-            int x, k;
-            if (r_kfast) { x = e / BK; k = e % BK; } else { x = e % TILE; k = e / TILE; }
-            float val = 0.f;
-            if (r0 + x < a.nR && k0 + k < a.nK) val = fetch(a.R, learner, r0 + x, k0 + k);
-            Rs[k][x] = val;
-            if (c_kfast) { x = e / BK; k = e % BK; } else { x = e % TILE; k = e / TILE; }
-            val = 0.f;
-            if (c0 + x < a.nC && k0 + k < a.nK) val = fetch(a.C, learner, c0 + x, k0 + k);
-            Cs[k][x] = val;
+    for (int i = 0; i < NPER; ++i) {
+        rv_next[i] = mover_load(mr, a.R, learner, i, k_begin + mr.k[i], k_end);
+        cv_next[i] = mover_load(mc, a.C, learner, i, k_begin + mc.k[i], k_end);
+    }
+    for (int k0 = k_begin; k0 < k_end; k0 += BK) {
+#pragma unroll
+        for (int i = 0; i < NPER; ++i) {
+            Rs[mr.k[i]][mr.x[i]] = rv_next[i];
+            Cs[mc.k[i]][mc.x[i]] = cv_next[i];
         }
         __syncthreads();
+        if (k0 + BK < k_end) {
+#pragma unroll
+            for (int i = 0; i < NPER; ++i) {      // next slice in flight during the FMAs
+                rv_next[i] = mover_load(mr, a.R, learner, i, k0 + BK + mr.k[i], k_end);
+                cv_next[i] = mover_load(mc, a.C, learner, i, k0 + BK + mc.k[i], k_end);
+            }
+        }
 #pragma unroll
         for (int k = 0; k < BK; ++k) {
             float rv[4], cv[4];
@@ -111,6 +153,8 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(Args a) {
                 float z = acc[i][j] + a.bias[(size_t)learner * a.bias_stride + c];
                 if (a.relu) z = fmaxf(z, 0.f);
                 a.out[(size_t)learner * a.out_stride + (size_t)r * a.ld_out + c] = z;
+            } else if (EPI == EPI_PARTIAL) {
+                a.out[(size_t)split * a.split_stride + (size_t)learner * a.out_stride + (size_t)r * a.ld_out + c] = acc[i][j];
             } else if (EPI == EPI_BWD) {
                 const float m = a.mask[(size_t)learner * a.mask_stride + (size_t)r * a.ld_mask + c];
                 a.out[(size_t)learner * a.out_stride + (size_t)r * a.ld_out + c] = m > 0.f ? acc[i][j] : 0.f;
@@ -134,14 +178,49 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(Args a) {
     }
 }
 
+// out[j][r][c] = act(sum_s partial[s][j][r][c] + bias[j][c]), splits added in ascending order
+__global__ void __launch_bounds__(256)
+finish_forward_kernel(const float* __restrict__ partial, size_t split_stride, int splits, const float* __restrict__ bias,
+                      size_t bias_stride, float* __restrict__ out, int P, int B, int ld_out, int nC, int relu) {
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t per_learner = (size_t)B * ld_out;
+    if (e >= (size_t)P * per_learner) return;
+    const int c = (int)(e % ld_out);
+    if (c >= nC) return;
+    const int learner = (int)(e / per_learner);
+    float z = 0.f;
+    for (int s = 0; s < splits; ++s) z += partial[(size_t)s * split_stride + e];
+    z += bias[(size_t)learner * bias_stride + c];
+    if (relu) z = fmaxf(z, 0.f);
+    out[e] = z;
+}
+
 template <int EPI>
-hipError_t run(const Args& a, int P, hipStream_t st) {
-    dim3 grid((a.nC + TILE - 1) / TILE, (a.nR + TILE - 1) / TILE, P);
+hipError_t run(const Args& a, int P, int splits, hipStream_t st) {
+    dim3 grid((a.nC + TILE - 1) / TILE, (a.nR + TILE - 1) / TILE, P * splits);
     hipLaunchKernelGGL(gemm_f32_kernel<EPI>, grid, dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
 }  // namespace
+
+// How the forward pass of a layer splits its contraction: returns the number of splits and the
+// contraction range of each (a multiple of the slice length).  Depends on the shapes only.
+int f32_forward_plan(int P, int B, int d_in, int d_out, int* chunk_out) {
+    const long tiles = (long)((B + TILE - 1) / TILE) * ((d_out + TILE - 1) / TILE) * P;
+    long s = 1;
+    if (tiles < 256 && d_in > 4 * BK) {
+        s = (512 + tiles - 1) / tiles;               // aim at ~512 workgroups
+        const long max_s = d_in / (2 * BK);          // at least two slices per split
+        if (s > max_s) s = max_s;
+        if (s > 64) s = 64;
+        if (s < 1) s = 1;
+    }
+    int chunk = (int)((d_in + s - 1) / s);
+    chunk = (chunk + BK - 1) / BK * BK;
+    if (chunk_out) *chunk_out = chunk;
+    return (d_in + chunk - 1) / chunk;               // splits that actually receive work
+}
 
 hipError_t f32_forward(const LayerCall& c, hipStream_t st) {
     Args a = {};
@@ -152,17 +231,32 @@ hipError_t f32_forward(const LayerCall& c, hipStream_t st) {
     a.out = (float*)c.out; a.out_stride = c.out_stride; a.ld_out = c.ld_out;
     a.bias = c.b; a.bias_stride = c.w_stride;
     a.relu = c.relu;
-    return run<EPI_FWD>(a, c.P, st);
+    int chunk = 0;
+    const int splits = f32_forward_plan(c.P, c.B, c.d_in, c.d_out, &chunk);
+    if (splits == 1 || !c.scratch) {
+        a.k_chunk = a.nK;
+        return run<EPI_FWD>(a, c.P, 1, st);
+    }
+    a.k_chunk = chunk;
+    a.out = (float*)c.scratch;
+    a.split_stride = (size_t)c.P * c.out_stride;
+    hipError_t e = run<EPI_PARTIAL>(a, c.P, splits, st);
+    if (e != hipSuccess) return e;
+    const size_t total = (size_t)c.P * c.out_stride;
+    hipLaunchKernelGGL(finish_forward_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       (const float*)c.scratch, a.split_stride, splits, c.b, c.w_stride, (float*)c.out, c.P, c.B,
+                       c.ld_out, c.d_out, c.relu);
+    return hipGetLastError();
 }
 
 hipError_t f32_backward_data(const LayerCall& c, hipStream_t st) {
     Args a = {};
     a.R = {(const float*)c.dz, c.dz_stride, c.ld_dz, 1, nullptr, 0, 0};
     a.C = {c.w, c.w_stride, 1, c.d_in, nullptr, 0, 0};  // Cm(c = input unit, k = output unit) = W[k][c]
-    a.nR = c.B; a.nC = c.d_in; a.nK = c.d_out;
+    a.nR = c.B; a.nC = c.d_in; a.nK = c.d_out; a.k_chunk = a.nK;
     a.out = (float*)c.dz_prev; a.out_stride = c.dz_prev_stride; a.ld_out = c.ld_in;
     a.mask = (const float*)c.in; a.mask_stride = c.in_stride; a.ld_mask = c.ld_in;
-    return run<EPI_BWD>(a, c.P, st);
+    return run<EPI_BWD>(a, c.P, 1, st);
 }
 
 hipError_t f32_update(const LayerCall& c, hipStream_t st) {
@@ -170,12 +264,12 @@ hipError_t f32_update(const LayerCall& c, hipStream_t st) {
     a.R = {(const float*)c.dz, c.dz_stride, 1, c.ld_dz, nullptr, 0, 0};        // R(r = unit, k = sample) = dZ[k][r]
     a.C = {(const float*)c.in, c.in_stride, 1, c.ld_in, c.gather, c.gather_stride, 1};  // Cm(c, k = sample) = A[k][c]
     if (c.gather) a.C.learner_stride = 0;
-    a.nR = c.d_out; a.nC = c.d_in; a.nK = c.B;
+    a.nR = c.d_out; a.nC = c.d_in; a.nK = c.B; a.k_chunk = a.nK;
     a.out = c.w; a.out_stride = c.w_stride; a.ld_out = c.d_in;
     a.bias_rw = c.b; a.bias_stride = c.w_stride;
     a.dz = (const float*)c.dz; a.dz_stride = c.dz_stride; a.ld_dz = c.ld_dz;
     a.lr = c.lr;
-    return run<EPI_UPD>(a, c.P, st);
+    return run<EPI_UPD>(a, c.P, 1, st);
 }
 
 }  // namespace kavg

@@ -24,7 +24,7 @@ struct Layout {
     size_t n = 0, stride = 0;          // parameters per replica, padded replica stride (elements)
     int ldz = 0;                       // padded class count (logits / dZ_L leading dimension)
     size_t off_w = 0, off_v = 0, off_reps = 0, off_shadow = 0, off_idx = 0, off_flag = 0;
-    size_t off_logits = 0, off_rowloss = 0, off_losses = 0;
+    size_t off_logits = 0, off_rowloss = 0, off_losses = 0, off_scratch = 0;
     std::vector<size_t> off_act, off_dz;   // per layer l = 1..L (index l-1); act of the last layer unused
     std::vector<size_t> w_off, b_off;      // parameter offsets inside a replica
     size_t total = 0;
@@ -70,6 +70,15 @@ Layout make_layout(int P, int K, int B, int L, const int* dims, int dtype) {
     lo.off_logits = take((size_t)P * B * lo.ldz * 4);
     lo.off_rowloss = take((size_t)K * P * B * 4);
     lo.off_losses = take((size_t)K * P * 4);
+    if (dtype == KAVG_FP32) {          // partial tiles of the split forward contractions
+        size_t need = 0;
+        for (int l = 1; l <= L; ++l) {
+            const int splits = f32_forward_plan(P, B, dims[l - 1], dims[l], nullptr);
+            const size_t ld = l == L ? (size_t)lo.ldz : (size_t)dims[l];
+            if (splits > 1 && (size_t)splits * P * B * ld * 4 > need) need = (size_t)splits * P * B * ld * 4;
+        }
+        lo.off_scratch = need ? take(need) : 0;
+    }
     lo.total = p;
     return lo;
 }
@@ -205,6 +214,7 @@ LayerCall layer_call(const kavg_ctx* c, int l /*1..L*/, int k) {
     q.dz = c->ws + lo.off_dz[l - 1]; q.ld_dz = l == L ? lo.ldz : c->dims[l];
     q.dz_stride = (size_t)c->B * q.ld_dz;
     q.lr = c->lr;
+    q.scratch = c->lo.off_scratch ? c->ws + c->lo.off_scratch : nullptr;
     (void)esz;
     return q;
 }

@@ -53,10 +53,13 @@ struct LayerCall {
     // gradient w.r.t. the previous layer's pre-activation (output of backward-data): [P][B][ld_in]
     void* dz_prev; size_t dz_prev_stride;
     int relu;              // forward: apply ReLU (hidden layer) / keep fp32 logits (last layer)
+    void* scratch;         // fp32 forward: partial tiles of a split contraction (see f32_forward_plan)
     float lr;
 };
 
 // fp32 path
+// splits of the forward contraction of a layer and the contraction range of each; shapes only
+int f32_forward_plan(int P, int B, int d_in, int d_out, int* chunk_out);
 hipError_t f32_forward(const LayerCall& c, hipStream_t st);
 hipError_t f32_backward_data(const LayerCall& c, hipStream_t st);
 hipError_t f32_update(const LayerCall& c, hipStream_t st);
