@@ -236,3 +236,80 @@ def test_state_errors():
         g.set_data(X, ybad)
     assert ei.value.code == kavg.KAVG_EINVAL
     g.close()
+
+
+# ----------------------------------------------------------------- edge cases
+@pytest.mark.parametrize("bf16", [False, True], ids=["fp32", "bf16"])
+@pytest.mark.parametrize("P,K,B,dims", [
+    (1, 1, 1, (8, 8, 2)),                  # one learner, one step, one sample
+    (1, 3, 2, (16, 3)),                    # single layer, fewer classes than any tile
+    (5, 1, 3, (1000, 72, 10)),             # long first contraction (split over workgroups in fp32)
+])
+def test_degenerate_shapes(bf16, P, K, B, dims):
+    g, o = _pair(P, K, 0.05, 0.5, dims, B, bf16, seed=71, N=37)
+    _run_and_compare(g, o, dims, rounds=2, tol=TOL_BF16 if bf16 else TOL_FP32, tag="edge %s" % (dims,))
+    g.close()
+
+
+def test_bf16_two_runs_are_bit_identical():
+    dims = (264, 200, 136, 10)
+    outs = []
+    for _ in range(2):
+        g, _o = _pair(3, 3, 0.05, 0.9, dims, 40, True, seed=81)
+        for _r in range(2):
+            g.local_steps()
+            g.meta_update()
+        outs.append((g.params(), g.momentum(), g.losses(), g.replica(1)))
+        g.close()
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["fp32", "bf16"])
+def test_resume_from_saved_state_continues_bit_identically(bf16):
+    dims = (72, 40, 6)
+    g, o = _pair(3, 2, 0.05, 0.9, dims, 12, bf16, seed=91)
+    for _ in range(2):
+        g.local_steps()
+        g.meta_update()
+    w, v, r = g.params(), g.momentum(), g.round()
+    g.local_steps()
+    g.meta_update()
+    want_w, want_v, want_idx = g.params(), g.momentum(), g.indices()
+    g.close()
+    h, _o = _pair(3, 2, 0.05, 0.9, dims, 12, bf16, seed=91)      # same data, same index seed
+    h.set_state(w, v, r)
+    assert h.round() == 2
+    h.local_steps()
+    h.meta_update()
+    assert np.array_equal(h.indices(), want_idx)                 # the stream resumes at step round*K
+    assert np.array_equal(h.params(), want_w) and np.array_equal(h.momentum(), want_v)
+    h.close()
+
+
+def test_mu_zero_is_plain_averaging():
+    """mu = 0: M-AVG reduces to K-AVG (remark after Theorem 1): the new global model is the
+    average of the replicas."""
+    dims = (40, 24, 6)
+    g, o = _pair(4, 2, 0.1, 0.0, dims, 9, False, seed=95)
+    g.local_steps()
+    reps = np.stack([g.replica(j) for j in range(4)]).astype(np.float64)
+    g.meta_update()
+    assert flat_error(g.params(), reps.mean(axis=0)) < 1e-6
+    g.close()
+
+
+def test_profile_counts_launches():
+    dims = (40, 24, 6)
+    g, _o = _pair(2, 3, 0.1, 0.5, dims, 9, False, seed=97)
+    g.profile(["forward", "update", "meta"], every=1)
+    g.local_steps()
+    g.meta_update()
+    got = g.profile_read()
+    assert got["forward"][1] == 3 * 2 and got["update"][1] == 3 * 2 and got["meta"][1] == 1
+    assert got["backward"][1] == 0 and got["forward"][0] > 0.0
+    g.profile(["update"], every=4)
+    g.local_steps()
+    assert g.profile_read()["update"][1] == 2                    # launches 0 and 4 of 6
+    g.profile([])
+    g.close()
