@@ -87,21 +87,25 @@ def stored_traffic(kernel_class):
     return rec.get("traffic_bytes_per_launch", {}).get(kernel_class)
 
 
-def cpu_baseline(w, data, learners):
-    """The oracle on `learners` learners x K steps of this workload."""
+def cpu_baseline(w, data, learners, rounds):
+    """The oracle, as it stands, on `rounds` meta rounds of this workload restricted to its first
+    `learners` learners (learners are independent between meta steps, so the rate per
+    learner-sample is that of the full workload)."""
     from threadpoolctl import threadpool_info
     from oracle import mavg_oracle as O
-    o = O.MAvgOracle(w.P, w.K, w.lr, w.mu, w.dims, w.B, bf16=(w.dtype == kavg.KAVG_BF16),
+    o = O.MAvgOracle(learners, w.K, w.lr, w.mu, w.dims, w.B, bf16=(w.dtype == kavg.KAVG_BF16),
                      index_seed=w.seeds["index"])
     o.set_data(data["X32"], data["y"])
     o.set_params(data["w0"])
     t0 = time.perf_counter()
-    o.local_steps(learners=list(range(learners)))
+    for _ in range(rounds):
+        o.local_steps()
+        o.meta_update()
     dt = time.perf_counter() - t0
     threads = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
-    return {"value": learners * w.K * w.B / dt, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
-            "sample": "%d of %d learners x K=%d local steps of the same workload (%.1f s)" % (
-                learners, w.P, w.K, dt)}
+    return {"value": rounds * learners * w.K * w.B / dt, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d meta rounds of the same workload with %d of its %d learners (%.1f s of CPU time)" % (
+                rounds, learners, w.P, dt)}
 
 
 def bench_meta_only(torch, passes=200, warmup=5):
@@ -126,7 +130,18 @@ def bench_meta_only(torch, passes=200, warmup=5):
     ms = ev0.elapsed_time(ev1) / passes
     bytes_pass = (2 * P + 4) * 4 * n
     gbs = bytes_pass / (ms * 1e-3) / 1e9
-    return {"workload": "meta_only: P=%d replicas of n=%d fp32, mu=%.2f, %d passes" % (P, n, w.mu, passes),
+    # context: what a plain device copy of the same replica block reaches on this machine (same 1:1
+    # read/write mix as the meta step)
+    dst = torch.empty_like(reps)
+    for _ in range(3):
+        dst.copy_(reps)
+    ev0.record()
+    for _ in range(20):
+        dst.copy_(reps)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * reps.numel() * 4 / (ev0.elapsed_time(ev1) / 20 * 1e-3) / 1e9
+    return {"plain_copy_GBps": copy_gbs, "workload": "meta_only: P=%d replicas of n=%d fp32, mu=%.2f, %d passes" % (P, n, w.mu, passes),
             "ms_per_pass": ms, "bytes_per_pass": bytes_pass, "GBps": gbs, "peak_GBps": HBM_PEAK_GBS,
             "frac": gbs / HBM_PEAK_GBS}
 
@@ -139,7 +154,8 @@ def main():
     ap.add_argument("--workload", default="cifar_mlp", choices=[k for k, v in WORKLOADS.items() if v.dims])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-meta-only", action="store_true")
-    ap.add_argument("--cpu-learners", type=int, default=3)
+    ap.add_argument("--cpu-learners", type=int, default=16)
+    ap.add_argument("--cpu-rounds", type=int, default=3)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (reference dispatch for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -248,7 +264,7 @@ def main():
         torch.cuda.empty_cache()
         out["meta_update"] = bench_meta_only(torch)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, data, min(args.cpu_learners, w.P))
+        out["cpu_baseline"] = cpu_baseline(w, data, min(args.cpu_learners, w.P), args.cpu_rounds)
     print(json.dumps(out))
 
 
