@@ -44,11 +44,16 @@ def class_model(w):
     bf = w.dtype == kavg.KAVG_BF16
     e = 2 if bf else 4                      # operand element size
     ldz = (d[L] + 7) // 8 * 8
+    head = d[L] <= 16       # few classes: the last layer's forward and data gradient run inside the loss kernel
     by = {"forward": 0, "backward": 0, "update": 0}
     fl = {"forward": 0, "backward": 0, "update": 0}
     for l in range(1, L + 1):
         wsz = d[l] * d[l - 1]
         ld_out = ldz if l == L else d[l]
+        if head and l == L:
+            by["update"] += P * ((8 + (2 if bf else 0)) * wsz + 8 * d[l] + e * B * (ld_out + d[l - 1]))
+            fl["update"] += P * 2 * B * wsz
+            continue
         # forward: weights once, bias, input rows, output rows
         by["forward"] += P * (e * wsz + 4 * d[l] + e * B * d[l - 1] + (4 * B * ld_out if l == L else e * B * d[l]))
         fl["forward"] += P * 2 * B * wsz
@@ -216,7 +221,10 @@ def main():
     ms_sampled, sampled = prof[heavy]
     per_round = w.K if heavy != "meta" else 1
     n_layers = len(w.dims) - 1
-    launches = (1 if heavy == "meta" else (n_layers - 1 if heavy == "backward" else n_layers)) * per_round * args.steps
+    head = w.dims[-1] <= 16
+    per_step = {"meta": 1, "update": n_layers, "forward": n_layers - (1 if head else 0),
+                "backward": n_layers - 1 - (1 if head else 0)}[heavy]
+    launches = per_step * per_round * args.steps
     ms_heavy = ms_sampled / max(sampled, 1) * launches         # sampled mean launch time x all launches of the class
     bytes_heavy = by[heavy] * per_round * args.steps           # all launches of the class in the timed region
     flops_heavy = fl[heavy] * per_round * args.steps

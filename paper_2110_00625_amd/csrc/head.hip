@@ -1,0 +1,342 @@
+// Classifier head for small class counts (C <= 16), both precisions.
+//
+// With ten classes the last layer is a sliver: its forward product, the
+// softmax cross-entropy, its data gradient and its weight update together
+// move a few hundred KB per learner, and as four generic launches they cost
+// four launch-plus-pipeline latencies.  Two kernels replace them:
+//
+//  head_forward_backward   one wavefront per sample row:
+//        z = A_{L-1}[s] W_L^T + b_L                     (lanes split the contraction, butterfly sum)
+//        loss_s = -log softmax(z)[y_s],  dZ_L[s] = (softmax(z) - onehot(y_s)) / B   (the 1/B_n of Algorithm 1)
+//        dZ_{L-1}[s] = (dZ_L[s] W_L) * [A_{L-1}[s] > 0]
+//  head_update             W_L <- W_L - lr * dZ_L^T A_{L-1},  b_L <- b_L - lr * colsum(dZ_L)
+//        (the learner update of Algorithm 1 for the last layer; runs after the kernel above
+//        because that one reads the weights of before the step)
+//
+// Mixed precision follows the same rounding points as the generic kernels:
+// products of bf16 operands accumulated in fp32, dZ_L and dZ_{L-1} rounded to
+// bf16 (round to nearest even) before any use, logits / softmax / loss / bias
+// / master update in fp32, shadow refreshed from the updated master.
+#include "kavg_internal.h"
+
+namespace kavg {
+
+namespace {
+
+constexpr int CMAX = 16;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float wave_sum(float x) {
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+__device__ __forceinline__ uint16_t bf16_bits(float x) {
+    __bf16 h = (__bf16)x;                         // round to nearest even
+    return __builtin_bit_cast(uint16_t, h);
+}
+__device__ __forceinline__ float bf16_round(float x) {
+    return __builtin_bit_cast(float, (uint32_t)bf16_bits(x) << 16);
+}
+
+// A "piece" is what one lane loads at once: 8 bf16 or 1 float.
+template <bool BF16> struct Piece;
+template <> struct Piece<true> {
+    static constexpr int N = 8;
+    float v[8];
+    __device__ __forceinline__ void load(const void* base, size_t elem) {
+        const u32x4 r = *(const u32x4*)((const uint16_t*)base + elem);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __builtin_bit_cast(float, r[i] << 16);
+            v[2 * i + 1] = __builtin_bit_cast(float, r[i] & 0xFFFF0000u);
+        }
+    }
+};
+template <> struct Piece<false> {
+    static constexpr int N = 1;
+    float v[1];
+    __device__ __forceinline__ void load(const void* base, size_t elem) { v[0] = ((const float*)base)[elem]; }
+};
+
+struct HeadArgs {
+    const void* act; int ld_act; size_t act_lstride;      // A_{L-1} [P][B][ld_act], or the data set when gather != null
+    const int32_t* gather; long gather_lstride;           // row s of learner j is data row gather[j*gather_lstride + s]
+    const void* wmul; size_t wmul_lstride;                // weights as multiplied: bf16 shadow or fp32 master, [C][d]
+    float* wmaster; size_t w_lstride;                     // fp32 master of the same layer
+    uint16_t* wshadow; size_t ws_lstride;                 // bf16 shadow to refresh (null in fp32)
+    float* bias;                                          // fp32 master bias (stride w_lstride)
+    const int32_t* y;                                     // labels of the data set
+    void* dz; int ldz; size_t dz_lstride;                 // dZ_L [P][B][ldz]
+    void* dz_prev; size_t dz_prev_lstride;                // dZ_{L-1} [P][B][d], null for a single-layer model
+    float* rowloss;                                       // [P][B]
+    int P, B, d, C;
+    float lr;
+};
+
+// CT = compile-time bound on the class count (4, 8, 12 or 16): every loop over classes is fully
+// unrolled and its loads are issued unconditionally (rows beyond C re-read row C-1 and are ignored),
+// so that a lane's loads of a step go out together instead of one round trip per class.
+template <bool BF16, int CT>
+__global__ void __launch_bounds__(256) head_forward_backward_kernel(HeadArgs a) {
+    constexpr int N = Piece<BF16>::N;
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);      // one wavefront per sample row
+    const int learner = blockIdx.y;
+    if (row >= a.B) return;                                   // whole wavefront leaves together
+    const int32_t* g = a.gather + (long)learner * a.gather_lstride;
+    const int sample = g[row];                                // data row of this sample (labels; inputs when L = 1)
+    const size_t arow = a.act_lstride ? (size_t)learner * a.act_lstride + (size_t)row * a.ld_act
+                                      : (size_t)sample * a.ld_act;
+    const void* W = BF16 ? (const void*)((const uint16_t*)a.wmul + (size_t)learner * a.wmul_lstride)
+                         : (const void*)((const float*)a.wmul + (size_t)learner * a.wmul_lstride);
+    const int pieces = a.d / N;
+    const int label_raw = a.y[sample];
+    float bias_c[CT];
+    {
+        const float* bias = a.bias + (size_t)learner * a.w_lstride;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) bias_c[c] = bias[c < a.C ? c : a.C - 1];
+    }
+    size_t wrow[CT];
+#pragma unroll
+    for (int c = 0; c < CT; ++c) wrow[c] = (size_t)(c < a.C ? c : a.C - 1) * a.d;
+
+    float acc[CT];
+#pragma unroll
+    for (int c = 0; c < CT; ++c) acc[c] = 0.f;
+    for (int q = lane; q < pieces; q += 64) {
+        Piece<BF16> x, w[CT];
+        x.load(a.act, arow + (size_t)q * N);
+#pragma unroll
+        for (int c = 0; c < CT; ++c) w[c].load(W, wrow[c] + (size_t)q * N);
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+#pragma unroll
+            for (int e = 0; e < N; ++e) acc[c] = fmaf(x.v[e], w[c].v[e], acc[c]);
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < CT; ++c) {
+        acc[c] = wave_sum(acc[c]) + bias_c[c];
+        if (c < a.C) mx = fmaxf(mx, acc[c]);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int c = 0; c < CT; ++c) if (c < a.C) sum += expf(acc[c] - mx);
+    const int label = label_raw < 0 ? 0 : (label_raw >= a.C ? a.C - 1 : label_raw);   // validated; never index outside
+    const float invB = 1.0f / (float)a.B;
+    float gz[CT];
+    float zy = 0.f;
+#pragma unroll
+    for (int c = 0; c < CT; ++c) {
+        gz[c] = 0.f;
+        if (c < a.C) {
+            const float p = expf(acc[c] - mx) / sum;
+            gz[c] = (p - (c == label ? 1.0f : 0.0f)) * invB;
+            if (BF16) gz[c] = bf16_round(gz[c]);
+            if (c == label) zy = acc[c];
+        }
+    }
+    if (lane == 0) a.rowloss[(size_t)learner * a.B + row] = -(zy - mx - logf(sum));
+    if (lane < a.ldz) {                                       // dZ_L row, pad columns zero
+        float mine = 0.f;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) if (c == lane) mine = gz[c];
+        const size_t at = (size_t)learner * a.dz_lstride + (size_t)row * a.ldz + lane;
+        if (BF16) ((uint16_t*)a.dz)[at] = bf16_bits(mine); else ((float*)a.dz)[at] = mine;
+    }
+    if (!a.dz_prev) return;
+
+    // dZ_{L-1}[s][k] = (sum_c dZ_L[s][c] W_L[c][k]) * [A_{L-1}[s][k] > 0]      (gz[c] = 0 beyond C)
+    for (int q = lane; q < pieces; q += 64) {
+        Piece<BF16> x, w[CT];
+        x.load(a.act, arow + (size_t)q * N);
+#pragma unroll
+        for (int c = 0; c < CT; ++c) w[c].load(W, wrow[c] + (size_t)q * N);
+        float da[N];
+#pragma unroll
+        for (int e = 0; e < N; ++e) da[e] = 0.f;
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+#pragma unroll
+            for (int e = 0; e < N; ++e) da[e] = fmaf(gz[c], w[c].v[e], da[e]);
+#pragma unroll
+        for (int e = 0; e < N; ++e) da[e] = x.v[e] > 0.f ? da[e] : 0.f;
+        const size_t at = (size_t)learner * a.dz_prev_lstride + (size_t)row * a.d + (size_t)q * N;
+        if (BF16) {
+            u32x4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = (uint32_t)bf16_bits(da[(2 * i) % N]) | ((uint32_t)bf16_bits(da[(2 * i + 1) % N]) << 16);
+            *(u32x4*)((uint16_t*)a.dz_prev + at) = o;
+        } else {
+            ((float*)a.dz_prev)[at] = da[0];
+        }
+    }
+}
+
+// One row of dZ_L (ldz <= 16 values) as floats; entries beyond ldz are zero.
+template <bool BF16>
+__device__ __forceinline__ void load_dz_row(const void* dz, size_t at, int ldz, float* out /*[16]*/) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) out[i] = 0.f;
+    if (BF16) {
+        const u32x4 lo = *(const u32x4*)((const uint16_t*)dz + at);
+        u32x4 hi = {0u, 0u, 0u, 0u};
+        if (ldz > 8) hi = *(const u32x4*)((const uint16_t*)dz + at + 8);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = __builtin_bit_cast(float, lo[i] << 16);
+            out[2 * i + 1] = __builtin_bit_cast(float, lo[i] & 0xFFFF0000u);
+            out[8 + 2 * i] = __builtin_bit_cast(float, hi[i] << 16);
+            out[8 + 2 * i + 1] = __builtin_bit_cast(float, hi[i] & 0xFFFF0000u);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (4 * i < ldz) {                                // ldz is a multiple of 8
+                const f32x4 v = *(const f32x4*)((const float*)dz + at + 4 * i);
+                out[4 * i] = v.x; out[4 * i + 1] = v.y; out[4 * i + 2] = v.z; out[4 * i + 3] = v.w;
+            }
+        }
+    }
+}
+
+// 256 threads = 4 wavefronts.  Lane = 4*g + pl: sample group g (samples s = g mod 16) and piece
+// blockIdx.x*16 + 4*wave + pl of the layer's input units.  Every lane sums dZ_L[s][c] * A[s][piece]
+// over its samples in ascending order; a butterfly over the group bits of the lane index adds the
+// sixteen groups, after which lane group g applies the update of class c = g.
+template <bool BF16, int CT>
+__global__ void __launch_bounds__(256) head_update_kernel(HeadArgs a) {
+    constexpr int N = Piece<BF16>::N;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int grp = lane >> 2, pl = lane & 3;
+    const int q = blockIdx.x * 16 + wave * 4 + pl;
+    const int learner = blockIdx.y;
+    const int pieces = a.d / N;
+    const bool live = q < pieces;
+    const int qq = live ? q : pieces - 1;                     // out-of-range lanes shadow the last piece, never store
+    const int32_t* g = a.gather + (long)learner * a.gather_lstride;
+
+    float acc[CT][N], bsum[CT];
+#pragma unroll
+    for (int c = 0; c < CT; ++c) {
+        bsum[c] = 0.f;
+#pragma unroll
+        for (int e = 0; e < N; ++e) acc[c][e] = 0.f;
+    }
+    for (int s = grp; s < a.B; s += 16) {
+        const size_t arow = a.act_lstride ? (size_t)learner * a.act_lstride + (size_t)s * a.ld_act
+                                          : (size_t)g[s] * a.ld_act;
+        Piece<BF16> x;
+        x.load(a.act, arow + (size_t)qq * N);
+        float gz[16];
+        load_dz_row<BF16>(a.dz, (size_t)learner * a.dz_lstride + (size_t)s * a.ldz, a.ldz, gz);
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            bsum[c] += gz[c];                                  // bias gradient: column sum of dZ_L
+#pragma unroll
+            for (int e = 0; e < N; ++e) acc[c][e] = fmaf(gz[c], x.v[e], acc[c][e]);
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CT; ++c) {
+        float b = bsum[c];
+        b += __shfl_xor(b, 4, 64); b += __shfl_xor(b, 8, 64); b += __shfl_xor(b, 16, 64); b += __shfl_xor(b, 32, 64);
+        bsum[c] = b;
+#pragma unroll
+        for (int e = 0; e < N; ++e) {
+            float v = acc[c][e];
+            v += __shfl_xor(v, 4, 64);
+            v += __shfl_xor(v, 8, 64);
+            v += __shfl_xor(v, 16, 64);
+            v += __shfl_xor(v, 32, 64);
+            acc[c][e] = v;
+        }
+    }
+    if (live && grp < a.C) {
+        float mine[N];
+#pragma unroll
+        for (int e = 0; e < N; ++e) mine[e] = 0.f;
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+            if (c == grp) {
+#pragma unroll
+                for (int e = 0; e < N; ++e) mine[e] = acc[c][e];
+            }
+        float* wm = a.wmaster + (size_t)learner * a.w_lstride + (size_t)grp * a.d + (size_t)q * N;
+        float w[N];
+#pragma unroll
+        for (int e = 0; e < N; ++e) w[e] = wm[e] - a.lr * mine[e];
+#pragma unroll
+        for (int e = 0; e < N; ++e) wm[e] = w[e];
+        if (BF16) {
+            u32x4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = (uint32_t)bf16_bits(w[(2 * i) % N]) | ((uint32_t)bf16_bits(w[(2 * i + 1) % N]) << 16);
+            *(u32x4*)(a.wshadow + (size_t)learner * a.ws_lstride + (size_t)grp * a.d + (size_t)q * N) = o;
+        }
+    }
+    if (blockIdx.x == 0 && wave == 0 && pl == 0 && grp < a.C) {   // every lane holds the full column sums
+        float mine = 0.f;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) if (c == grp) mine = bsum[c];
+        float* b = a.bias + (size_t)learner * a.w_lstride + grp;
+        *b = *b - a.lr * mine;
+    }
+}
+
+HeadArgs make_args(const LayerCall& c, const int32_t* y, const int32_t* idx, long idx_lstride, float* rowloss, bool bf16) {
+    HeadArgs a = {};
+    a.act = c.in; a.ld_act = c.ld_in; a.act_lstride = c.gather ? 0 : c.in_stride;
+    a.gather = idx; a.gather_lstride = idx_lstride;
+    a.wmul = bf16 ? (const void*)c.ws : (const void*)c.w;
+    a.wmul_lstride = bf16 ? c.ws_stride : c.w_stride;
+    a.wmaster = c.w; a.w_lstride = c.w_stride; a.wshadow = bf16 ? c.ws : nullptr; a.ws_lstride = c.ws_stride;
+    a.bias = c.b; a.y = y;
+    a.dz = (void*)c.dz; a.ldz = c.ld_dz; a.dz_lstride = c.dz_stride;
+    a.dz_prev = c.dz_prev; a.dz_prev_lstride = c.dz_prev_stride;
+    a.rowloss = rowloss;
+    a.P = c.P; a.B = c.B; a.d = c.d_in; a.C = c.d_out; a.lr = c.lr;
+    return a;
+}
+
+}  // namespace
+
+bool head_supported(int C) { return C <= CMAX; }
+
+namespace {
+template <bool BF16>
+void launch_fb(const HeadArgs& a, dim3 grid, hipStream_t st) {
+    if (a.C <= 4) hipLaunchKernelGGL((head_forward_backward_kernel<BF16, 4>), grid, dim3(256), 0, st, a);
+    else if (a.C <= 8) hipLaunchKernelGGL((head_forward_backward_kernel<BF16, 8>), grid, dim3(256), 0, st, a);
+    else if (a.C <= 12) hipLaunchKernelGGL((head_forward_backward_kernel<BF16, 12>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((head_forward_backward_kernel<BF16, 16>), grid, dim3(256), 0, st, a);
+}
+template <bool BF16>
+void launch_upd(const HeadArgs& a, dim3 grid, hipStream_t st) {
+    if (a.C <= 4) hipLaunchKernelGGL((head_update_kernel<BF16, 4>), grid, dim3(256), 0, st, a);
+    else if (a.C <= 8) hipLaunchKernelGGL((head_update_kernel<BF16, 8>), grid, dim3(256), 0, st, a);
+    else if (a.C <= 12) hipLaunchKernelGGL((head_update_kernel<BF16, 12>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((head_update_kernel<BF16, 16>), grid, dim3(256), 0, st, a);
+}
+
+}  // namespace
+
+hipError_t head_forward_backward(const LayerCall& c, const int32_t* y, const int32_t* idx, long idx_lstride,
+                                 float* rowloss, int bf16, hipStream_t st) {
+    HeadArgs a = make_args(c, y, idx, idx_lstride, rowloss, bf16 != 0);
+    dim3 grid((c.B + 3) / 4, c.P);
+    if (bf16) launch_fb<true>(a, grid, st); else launch_fb<false>(a, grid, st);
+    return hipGetLastError();
+}
+
+hipError_t head_update(const LayerCall& c, const int32_t* idx, long idx_lstride, int bf16, hipStream_t st) {
+    HeadArgs a = make_args(c, nullptr, idx, idx_lstride, nullptr, bf16 != 0);
+    const int pieces = c.d_in / (bf16 ? 8 : 1);
+    dim3 grid((pieces + 15) / 16, c.P);
+    if (bf16) launch_upd<true>(a, grid, st); else launch_upd<false>(a, grid, st);
+    return hipGetLastError();
+}
+
+}  // namespace kavg

@@ -331,20 +331,34 @@ int kavg_local_steps(kavg_ctx* c) {
             KAVG_HIP(c, launch_index_stream(c->idx(), c->P, c->K, c->B, c->seed, c->t0, (uint32_t)c->N, st));
     }
 
+    // With few classes the last layer runs as two dedicated kernels (forward + loss + data gradient,
+    // then its update) instead of four generic launches.
+    const bool head = head_supported(c->dims[L]);
     for (int k = 0; k < c->K; ++k) {
-        for (int l = 1; l <= L; ++l) {                       // forward
+        const int32_t* idx_k = c->idx() + (size_t)k * c->B;
+        const long idx_ls = (long)c->K * c->B;
+        float* rowloss_k = c->rowloss() + (size_t)k * c->P * c->B;
+        for (int l = 1; l <= (head ? L - 1 : L); ++l) {      // forward
             LayerCall q = layer_call(c, l, k);
             Bracket br(c, KAVG_CLASS_FORWARD);
             KAVG_HIP(c, bf ? bf16_forward(q, st) : f32_forward(q, st));
         }
-        {
-        Bracket br(c, KAVG_CLASS_LOSS);
-        KAVG_HIP(c, launch_softmax_ce(c->logits(), c->lo.ldz, c->dims[L], c->y, c->idx() + (size_t)k * c->B,
-                                      (long)c->K * c->B, c->B, c->P, c->ws + c->lo.off_dz[L - 1], bf ? 1 : 0,
-                                      c->rowloss() + (size_t)k * c->P * c->B, st));
+        if (head) {
+            LayerCall q = layer_call(c, L, k);
+            Bracket br(c, KAVG_CLASS_LOSS);
+            KAVG_HIP(c, head_forward_backward(q, c->y, idx_k, idx_ls, rowloss_k, bf ? 1 : 0, st));
+        } else {
+            Bracket br(c, KAVG_CLASS_LOSS);
+            KAVG_HIP(c, launch_softmax_ce(c->logits(), c->lo.ldz, c->dims[L], c->y, idx_k, idx_ls, c->B, c->P,
+                                          c->ws + c->lo.off_dz[L - 1], bf ? 1 : 0, rowloss_k, st));
         }
         for (int l = L; l >= 1; --l) {                       // backward; W_l is read before it is updated
             LayerCall q = layer_call(c, l, k);
+            if (head && l == L) {
+                Bracket br(c, KAVG_CLASS_UPDATE);
+                KAVG_HIP(c, head_update(q, idx_k, idx_ls, bf ? 1 : 0, st));
+                continue;
+            }
             if (l > 1) {
                 Bracket br(c, KAVG_CLASS_BACKWARD);
                 KAVG_HIP(c, bf ? bf16_backward_data(q, st) : f32_backward_data(q, st));

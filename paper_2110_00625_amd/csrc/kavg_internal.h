@@ -68,4 +68,11 @@ hipError_t bf16_forward(const LayerCall& c, hipStream_t st);
 hipError_t bf16_backward_data(const LayerCall& c, hipStream_t st);
 hipError_t bf16_update(const LayerCall& c, hipStream_t st);
 
+// ---- classifier head for small class counts (last layer: forward + loss + data gradient, then update) ----
+bool head_supported(int C);
+// idx: this step's indices of learner 0, idx_lstride elements between learners
+hipError_t head_forward_backward(const LayerCall& c, const int32_t* y, const int32_t* idx, long idx_lstride,
+                                 float* rowloss, int bf16, hipStream_t st);
+hipError_t head_update(const LayerCall& c, const int32_t* idx, long idx_lstride, int bf16, hipStream_t st);
+
 }  // namespace kavg

@@ -299,14 +299,16 @@ def test_mu_zero_is_plain_averaging():
     g.close()
 
 
-def test_profile_counts_launches():
-    dims = (40, 24, 6)
+@pytest.mark.parametrize("dims,fwd_per_step", [((40, 24, 6), 1), ((40, 24, 20), 2)],
+                         ids=["head_kernels", "generic_last_layer"])
+def test_profile_counts_launches(dims, fwd_per_step):
+    # up to 16 classes the last layer's forward runs inside the loss kernel (one forward launch less)
     g, _o = _pair(2, 3, 0.1, 0.5, dims, 9, False, seed=97)
     g.profile(["forward", "update", "meta"], every=1)
     g.local_steps()
     g.meta_update()
     got = g.profile_read()
-    assert got["forward"][1] == 3 * 2 and got["update"][1] == 3 * 2 and got["meta"][1] == 1
+    assert got["forward"][1] == 3 * fwd_per_step and got["update"][1] == 3 * 2 and got["meta"][1] == 1
     assert got["backward"][1] == 0 and got["forward"][0] > 0.0
     g.profile(["update"], every=4)
     g.local_steps()
