@@ -36,13 +36,14 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
 FP32_PEAK_TFLOPS = 157.3
 
 
-def class_model(w):
+def class_model(w, learner_momentum=False):
     """Algorithmic bytes and flops of one launch-set (all layers) of each kernel
     class for ONE local step of all P learners, and of one meta pass."""
     P, B, d = w.P, w.B, w.dims
     L = len(d) - 1
     bf = w.dtype == kavg.KAVG_BF16
     e = 2 if bf else 4                      # operand element size
+    vel = 8 if learner_momentum else 0      # velocity read + write per parameter
     ldz = (d[L] + 7) // 8 * 8
     head = d[L] <= 16       # few classes: the last layer's forward and data gradient run inside the loss kernel
     by = {"forward": 0, "backward": 0, "update": 0}
@@ -51,14 +52,14 @@ def class_model(w):
         wsz = d[l] * d[l - 1]
         ld_out = ldz if l == L else d[l]
         if head and l == L:
-            by["update"] += P * ((8 + (2 if bf else 0)) * wsz + 8 * d[l] + e * B * (ld_out + d[l - 1]))
+            by["update"] += P * ((8 + vel + (2 if bf else 0)) * wsz + (8 + vel) * d[l] + e * B * (ld_out + d[l - 1]))
             fl["update"] += P * 2 * B * wsz
             continue
         # forward: weights once, bias, input rows, output rows
         by["forward"] += P * (e * wsz + 4 * d[l] + e * B * d[l - 1] + (4 * B * ld_out if l == L else e * B * d[l]))
         fl["forward"] += P * 2 * B * wsz
         # update: master read + write (+ shadow write), bias read + write, dZ and A once
-        by["update"] += P * ((8 + (2 if bf else 0)) * wsz + 8 * d[l] + e * B * (ld_out + d[l - 1]))
+        by["update"] += P * ((8 + vel + (2 if bf else 0)) * wsz + (8 + vel) * d[l] + e * B * (ld_out + d[l - 1]))
         fl["update"] += P * 2 * B * wsz
         if l > 1:   # data gradient: weights once, dZ_l, mask read, dZ_{l-1} written
             by["backward"] += P * (e * wsz + e * B * ld_out + 2 * e * B * d[l - 1])
@@ -92,14 +93,14 @@ def stored_traffic(kernel_class):
     return rec.get("traffic_bytes_per_launch", {}).get(kernel_class)
 
 
-def cpu_baseline(w, data, learners, rounds):
+def cpu_baseline(w, data, learners, rounds, beta=0.0):
     """The oracle, as it stands, on `rounds` meta rounds of this workload restricted to its first
     `learners` learners (learners are independent between meta steps, so the rate per
     learner-sample is that of the full workload)."""
     from threadpoolctl import threadpool_info
     from oracle import mavg_oracle as O
     o = O.MAvgOracle(learners, w.K, w.lr, w.mu, w.dims, w.B, bf16=(w.dtype == kavg.KAVG_BF16),
-                     index_seed=w.seeds["index"])
+                     index_seed=w.seeds["index"], learner_momentum=beta)
     o.set_data(data["X32"], data["y"])
     o.set_params(data["w0"])
     t0 = time.perf_counter()
@@ -161,6 +162,8 @@ def main():
     ap.add_argument("--no-meta-only", action="store_true")
     ap.add_argument("--cpu-learners", type=int, default=16)
     ap.add_argument("--cpu-rounds", type=int, default=3)
+    ap.add_argument("--learner-momentum", type=float, default=0.0,
+                    help="heavy-ball momentum inside every learner (variant of Section 2; default off = Algorithm 1)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (reference dispatch for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -182,6 +185,8 @@ def main():
     X = torch.from_numpy(data["Xbits"].view(np.int16) if bf else data["X32"]).cuda()
     y = torch.from_numpy(data["y"]).cuda()
     g.set_data(X, y)
+    if args.learner_momentum > 0:
+        g.set_learner_momentum(args.learner_momentum)
     g.set_params(data["w0"])
 
     if args.copy_calibration:
@@ -217,7 +222,7 @@ def main():
     loss_last = float(g.losses()[-1].mean())
 
     samples = w.P * w.K * w.B * args.steps
-    by, fl = class_model(w)
+    by, fl = class_model(w, args.learner_momentum > 0)
     ms_sampled, sampled = prof[heavy]
     per_round = w.K if heavy != "meta" else 1
     n_layers = len(w.dims) - 1
@@ -257,8 +262,9 @@ def main():
         "value": samples / dt, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if bf else "f32", "data": "synthetic",
-        "config": {"workload": "%s: P=%d K=%d B=%d mu=%g lr=%g MLP %s, N=%d" % (
-            w.name, w.P, w.K, w.B, w.mu, w.lr, "-".join(map(str, w.dims)), w.N),
+        "config": {"workload": "%s: P=%d K=%d B=%d mu=%g lr=%g MLP %s, N=%d%s" % (
+            w.name, w.P, w.K, w.B, w.mu, w.lr, "-".join(map(str, w.dims)), w.N,
+            ", learner momentum %g" % args.learner_momentum if args.learner_momentum > 0 else ""),
             "step": "one meta round = K local steps on P learners + fused meta step",
             "samples_per_step": w.P * w.K * w.B, "flops_per_step": flops_per_learner_step(w.dims, w.B) * w.P * w.K},
         "roofline": roof,
@@ -272,7 +278,7 @@ def main():
         torch.cuda.empty_cache()
         out["meta_update"] = bench_meta_only(torch)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, data, min(args.cpu_learners, w.P), args.cpu_rounds)
+        out["cpu_baseline"] = cpu_baseline(w, data, min(args.cpu_learners, w.P), args.cpu_rounds, args.learner_momentum)
     print(json.dumps(out))
 
 

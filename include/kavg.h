@@ -133,6 +133,20 @@ int kavg_losses(kavg_ctx* ctx, float* out_host);
 /* [P][K][B] indices used by the last kavg_local_steps */
 int kavg_indices(kavg_ctx* ctx, int32_t* out_host);
 
+/* Learner-level momentum.  Section 2 notes that momentum "can also" be added at
+ * the learner level (block momentum acts at the meta level); the form is not
+ * given, so heavy ball is taken: every learner j keeps a velocity u^j and its
+ * local step becomes  u <- beta u + g,  w <- w - lr u  (g = mean minibatch
+ * gradient).  u^j persists across meta rounds (it is not reset when the learner
+ * restarts from w~) and is zeroed by this call, kavg_set_params and
+ * kavg_set_state.  velocity_dev: device block of kavg_velocity_bytes(ctx) bytes,
+ * 256-byte aligned, BORROWED until kavg_destroy or until momentum is switched
+ * off again with beta = 0.  Errors: KAVG_EINVAL (beta outside [0,1), beta > 0
+ * without a buffer, misaligned), KAVG_ENOMEM (buffer too small). */
+size_t kavg_velocity_bytes(const kavg_ctx* ctx);
+int kavg_set_learner_momentum(kavg_ctx* ctx, float beta, void* velocity_dev, size_t bytes);
+int kavg_velocity(kavg_ctx* ctx, int j, float* out_host, size_t n);   /* u^j; KAVG_ESTATE when off */
+
 /* Measurement aid for callers that report per-kernel time (not part of the
  * method): while a class's bit is set in class_mask, one launch in `every` of
  * that class (the first, the every+1-th, ...) is bracketed by a HIP event pair

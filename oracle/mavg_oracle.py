@@ -30,6 +30,11 @@ Readings where the paper is silent (each repeated in the design notes):
 * momentum exactly as printed: no dampening, no Nesterov, block step 1;
   v persists across rounds;
 * 1/P is applied as a multiplication of the sum by the reciprocal.
+* learner-level momentum (Section 2 only says that momentum "can also" be added
+  at the learner level): heavy-ball inside each learner, u <- beta u + g,
+  w <- w - lr u, with g the mean minibatch gradient; every learner keeps its
+  own u across meta rounds (it is not reset when the learner restarts from
+  w~), u = 0 initially.  beta = 0 is Algorithm 1 as printed.
 * mixed precision ("bf16" mode): the operands of every matrix product are
   rounded to bf16 (nearest, ties to even): the weights as used in forward and
   data-gradient products, the stored hidden activations, and the gradient
@@ -189,8 +194,10 @@ def meta_step(w_tilde, v, replicas, mu):
 class MAvgOracle:
     """State machine with the same call names as the C library."""
 
-    def __init__(self, P, K, lr, mu, dims, B, bf16=False, index_seed=0):
+    def __init__(self, P, K, lr, mu, dims, B, bf16=False, index_seed=0, learner_momentum=0.0):
         assert P >= 1 and K >= 1 and B >= 1 and lr >= 0.0 and 0.0 <= mu < 1.0
+        assert 0.0 <= learner_momentum < 1.0
+        self.beta = float(learner_momentum)
         self.P, self.K, self.lr, self.mu = P, K, float(lr), float(mu)
         self.dims, self.B, self.bf16, self.seed = tuple(dims), B, bool(bf16), int(index_seed)
         self.n = num_params(self.dims)
@@ -210,6 +217,7 @@ class MAvgOracle:
         assert self.w_tilde.shape == (self.n,)
         self.v = np.zeros(self.n)
         self.reps = np.tile(self.w_tilde, (self.P, 1))
+        self.u = np.zeros((self.P, self.n)) if self.beta > 0.0 else None
         self.t0 = 0
         self.round = 0
 
@@ -217,6 +225,7 @@ class MAvgOracle:
         self.w_tilde = np.asarray(w, dtype=np.float64).copy()
         self.v = np.asarray(v, dtype=np.float64).copy()
         self.reps = np.tile(self.w_tilde, (self.P, 1))
+        self.u = np.zeros((self.P, self.n)) if self.beta > 0.0 else None
         self.round = int(round_)
         self.t0 = self.round * self.K
 
@@ -250,7 +259,11 @@ class MAvgOracle:
                 loss, g = minibatch_gradient(w, self.dims, Xb, yb, self.bf16)
                 losses[k, j] = loss
                 self.grad_sum += g
-                w -= self.lr * g          # in place: w is a view of replica j
+                if self.beta > 0.0:
+                    self.u[j] = self.beta * self.u[j] + g
+                    w -= self.lr * self.u[j]
+                else:
+                    w -= self.lr * g      # in place: w is a view of replica j
         self.t0 += self.K
         self.last_idx, self.last_losses = idx, losses
 
@@ -267,6 +280,9 @@ class MAvgOracle:
 
     def replica(self, j):
         return self.reps[j].copy()
+
+    def velocity(self, j):
+        return self.u[j].copy()
 
     def losses(self):
         return self.last_losses.copy()

@@ -76,6 +76,7 @@ struct Args {
     // update
     float* w; size_t w_lstride; uint16_t* ws; size_t ws_lstride; float* b;
     float lr;
+    float* u; float* ub; float beta;             // velocities of weights / bias (stride w_lstride), null: plain SGD
 };
 
 __device__ __forceinline__ uint16_t bf16_bits(float x) {
@@ -404,7 +405,13 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                 const f32x4 g = *(const f32x4*)(stage + (it * ROWS_PER_IT + rr) * SPITCH + cc);
                 if (r < a.nR && c < a.nC) {
                     f32x4 w = mst[i][it];
-                    w.x -= a.lr * g.x; w.y -= a.lr * g.y; w.z -= a.lr * g.z; w.w -= a.lr * g.w;
+                    f32x4 step = g;
+                    if (a.u) {                                  // heavy ball inside the learner
+                        f32x4* up = (f32x4*)(a.u + (size_t)learner * a.w_lstride + (size_t)r * a.nC + c);
+                        step = a.beta * (*up) + g;
+                        *up = step;
+                    }
+                    w.x -= a.lr * step.x; w.y -= a.lr * step.y; w.z -= a.lr * step.z; w.w -= a.lr * step.w;
                     *(f32x4*)(wbase + (size_t)r * a.nC + c) = w;
                     u32x2 o = {pack2(w.x, w.y), pack2(w.z, w.w)};
                     *(u32x2*)(sbase + (size_t)r * a.nC + c) = o;
@@ -412,8 +419,9 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
             }
         }
         if (tile_c == 0 && tid < TR && r0 + tid < a.nR) {
-            float* b = a.b + (size_t)learner * a.w_lstride + r0 + tid;
-            *b = *b - a.lr * bias_sum;
+            const size_t at = (size_t)learner * a.w_lstride + r0 + tid;
+            if (a.ub) { bias_sum = a.beta * a.ub[at] + bias_sum; a.ub[at] = bias_sum; }
+            a.b[at] = a.b[at] - a.lr * bias_sum;
         }
     }
 }
@@ -487,7 +495,7 @@ hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     a.C = {(const uint16_t*)c.in, c.gather ? 0 : c.in_stride, c.ld_in, 1, c.gather, c.gather_stride, c.B, c.d_in};
     a.nR = c.d_out; a.nC = c.d_in; a.nK = c.B;
     a.w = c.w; a.w_lstride = c.w_stride; a.ws = c.ws; a.ws_lstride = c.ws_stride; a.b = c.b;
-    a.lr = c.lr;
+    a.lr = c.lr; a.u = c.u; a.ub = c.ub; a.beta = c.beta;
     return launch<MODE_UPD, 128, 128, 2, 2, 1, 64, true, true, 1>(a, c.P, st);
 }
 

@@ -56,6 +56,7 @@ struct Args {
     const float* dz; size_t dz_stride; int ld_dz;      // UPD: dZ for the bias gradient [B][ld_dz]
     int relu;
     float lr;
+    float* u; float* ub; float beta;                   // UPD: velocities of weights / bias (null: plain SGD)
 };
 
 // Where thread `tid` finds its NPER elements of a slice: element i is (x, k) with the memory-
@@ -159,8 +160,10 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(Args a) {
                 const float m = a.mask[(size_t)learner * a.mask_stride + (size_t)r * a.ld_mask + c];
                 a.out[(size_t)learner * a.out_stride + (size_t)r * a.ld_out + c] = m > 0.f ? acc[i][j] : 0.f;
             } else {
-                float* w = a.out + (size_t)learner * a.out_stride + (size_t)r * a.ld_out + c;
-                *w = *w - a.lr * acc[i][j];
+                const size_t at = (size_t)learner * a.out_stride + (size_t)r * a.ld_out + c;
+                float g = acc[i][j];
+                if (a.u) { g = a.beta * a.u[at] + g; a.u[at] = g; }
+                a.out[at] = a.out[at] - a.lr * g;
             }
         }
     }
@@ -172,8 +175,9 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(Args a) {
             const float* dz = a.dz + (size_t)learner * a.dz_stride;
             float s = 0.f;
             for (int m = 0; m < a.nK; ++m) s += dz[(size_t)m * a.ld_dz + r];
-            float* b = a.bias_rw + (size_t)learner * a.bias_stride + r;
-            *b = *b - a.lr * s;
+            const size_t at = (size_t)learner * a.bias_stride + r;
+            if (a.ub) { s = a.beta * a.ub[at] + s; a.ub[at] = s; }
+            a.bias_rw[at] = a.bias_rw[at] - a.lr * s;
         }
     }
 }
@@ -268,7 +272,7 @@ hipError_t f32_update(const LayerCall& c, hipStream_t st) {
     a.out = c.w; a.out_stride = c.w_stride; a.ld_out = c.d_in;
     a.bias_rw = c.b; a.bias_stride = c.w_stride;
     a.dz = (const float*)c.dz; a.dz_stride = c.dz_stride; a.ld_dz = c.ld_dz;
-    a.lr = c.lr;
+    a.lr = c.lr; a.u = c.u; a.ub = c.ub; a.beta = c.beta;
     return run<EPI_UPD>(a, c.P, 1, st);
 }
 

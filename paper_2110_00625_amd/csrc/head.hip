@@ -72,6 +72,7 @@ struct HeadArgs {
     float* rowloss;                                       // [P][B]
     int P, B, d, C;
     float lr;
+    float* u; float* ub; float beta;                      // velocities of W_L / b_L (stride w_lstride), null: plain SGD
 };
 
 // CT = compile-time bound on the class count (4, 8, 12 or 16): every loop over classes is fully
@@ -264,7 +265,12 @@ __global__ void __launch_bounds__(256) head_update_kernel(HeadArgs a) {
 #pragma unroll
                 for (int e = 0; e < N; ++e) mine[e] = acc[c][e];
             }
-        float* wm = a.wmaster + (size_t)learner * a.w_lstride + (size_t)grp * a.d + (size_t)q * N;
+        const size_t wat = (size_t)learner * a.w_lstride + (size_t)grp * a.d + (size_t)q * N;
+        float* wm = a.wmaster + wat;
+        if (a.u) {                                            // heavy ball inside the learner
+#pragma unroll
+            for (int e = 0; e < N; ++e) { mine[e] = a.beta * a.u[wat + e] + mine[e]; a.u[wat + e] = mine[e]; }
+        }
         float w[N];
 #pragma unroll
         for (int e = 0; e < N; ++e) w[e] = wm[e] - a.lr * mine[e];
@@ -281,8 +287,9 @@ __global__ void __launch_bounds__(256) head_update_kernel(HeadArgs a) {
         float mine = 0.f;
 #pragma unroll
         for (int c = 0; c < CT; ++c) if (c == grp) mine = bsum[c];
-        float* b = a.bias + (size_t)learner * a.w_lstride + grp;
-        *b = *b - a.lr * mine;
+        const size_t at = (size_t)learner * a.w_lstride + grp;
+        if (a.ub) { mine = a.beta * a.ub[at] + mine; a.ub[at] = mine; }
+        a.bias[at] = a.bias[at] - a.lr * mine;
     }
 }
 
@@ -298,6 +305,7 @@ HeadArgs make_args(const LayerCall& c, const int32_t* y, const int32_t* idx, lon
     a.dz_prev = c.dz_prev; a.dz_prev_lstride = c.dz_prev_stride;
     a.rowloss = rowloss;
     a.P = c.P; a.B = c.B; a.d = c.d_in; a.C = c.d_out; a.lr = c.lr;
+    a.u = c.u; a.ub = c.ub; a.beta = c.beta;
     return a;
 }
 

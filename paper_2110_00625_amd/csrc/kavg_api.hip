@@ -102,6 +102,8 @@ struct kavg_ctx {
     uint32_t t0;          // local steps every learner has taken
     uint64_t round;
     bool have_params, have_steps;
+    float beta;           // learner-level momentum, 0 = off
+    float* vel;           // [P][stride] velocities, caller memory, null = off
     char err[256];
     // measurement aid: HIP event pairs around the launches of selected kernel classes
     unsigned prof_mask;
@@ -161,6 +163,7 @@ int install_global(kavg_ctx* c, const float* w_host, const float* v_host) {
         KAVG_HIP(c, hipMemsetAsync(c->v(), 0, c->lo.stride * 4, c->stream));
     KAVG_HIP(c, launch_broadcast(c->w_tilde(), c->reps(), c->lo.stride, c->shadow(), c->lo.stride, c->P,
                                  c->lo.n, c->stream));
+    if (c->vel) KAVG_HIP(c, hipMemsetAsync(c->vel, 0, (size_t)c->P * c->lo.stride * 4, c->stream));
     KAVG_HIP(c, hipStreamSynchronize(c->stream));   // host buffers may be reused by the caller
     c->have_params = true;
     c->have_steps = false;
@@ -214,6 +217,9 @@ LayerCall layer_call(const kavg_ctx* c, int l /*1..L*/, int k) {
     q.dz = c->ws + lo.off_dz[l - 1]; q.ld_dz = l == L ? lo.ldz : c->dims[l];
     q.dz_stride = (size_t)c->B * q.ld_dz;
     q.lr = c->lr;
+    q.beta = c->beta;
+    q.u = c->vel ? c->vel + lo.w_off[l - 1] : nullptr;
+    q.ub = c->vel ? c->vel + lo.b_off[l - 1] : nullptr;
     q.scratch = c->lo.off_scratch ? c->ws + c->lo.off_scratch : nullptr;
     (void)esz;
     return q;
@@ -263,6 +269,7 @@ int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, co
     c->stream = (hipStream_t)hip_stream;
     c->X = nullptr; c->y = nullptr; c->N = 0; c->user_idx = nullptr;
     c->t0 = 0; c->round = 0; c->have_params = false; c->have_steps = false;
+    c->beta = 0.f; c->vel = nullptr;
     c->err[0] = 0;
     c->prof_mask = 0;
     c->prof_every = 1;
@@ -462,6 +469,33 @@ int kavg_profile_read(kavg_ctx* c, double* ms_out, long long* launches_out) {
     if (rc != KAVG_OK) return rc;
     for (int k = 0; k < KAVG_NCLASS; ++k) { ms_out[k] = c->prof_ms[k]; launches_out[k] = c->prof_launches[k]; }
     return KAVG_OK;
+}
+
+size_t kavg_velocity_bytes(const kavg_ctx* c) { return c ? (size_t)c->P * c->lo.stride * 4 : 0; }
+
+int kavg_set_learner_momentum(kavg_ctx* c, float beta, void* velocity_dev, size_t bytes) {
+    if (!c) return KAVG_EINVAL;
+    if (!(beta >= 0.f && beta < 1.f)) return fail(c, KAVG_EINVAL, "beta must lie in [0,1)");
+    if (beta == 0.f || !velocity_dev) {
+        if (beta != 0.f) return fail(c, KAVG_EINVAL, "beta > 0 needs a velocity buffer");
+        KAVG_HIP(c, hipStreamSynchronize(c->stream));
+        c->beta = 0.f; c->vel = nullptr;
+        return KAVG_OK;
+    }
+    if (((uintptr_t)velocity_dev % ALIGN) != 0) return fail(c, KAVG_EINVAL, "velocity buffer must be 256-byte aligned");
+    if (bytes < kavg_velocity_bytes(c)) return fail(c, KAVG_ENOMEM, "velocity buffer has %zu bytes, %zu needed", bytes, kavg_velocity_bytes(c));
+    KAVG_HIP(c, hipMemsetAsync(velocity_dev, 0, kavg_velocity_bytes(c), c->stream));
+    c->beta = beta; c->vel = (float*)velocity_dev;
+    return KAVG_OK;
+}
+
+int kavg_velocity(kavg_ctx* c, int j, float* out_host, size_t n) {
+    if (!c) return KAVG_EINVAL;
+    if (!out_host || n != c->lo.n) return fail(c, KAVG_EINVAL, "need a buffer of exactly %zu floats", c->lo.n);
+    if (j < 0 || j >= c->P) return fail(c, KAVG_EINVAL, "learner %d outside [0,%d)", j, c->P);
+    if (!c->vel) return fail(c, KAVG_ESTATE, "learner-level momentum is off");
+    KAVG_HIP(c, hipMemcpyAsync(out_host, c->vel + (size_t)j * c->lo.stride, n * 4, hipMemcpyDeviceToHost, c->stream));
+    return sync_and_check(c);
 }
 
 uint64_t kavg_round(const kavg_ctx* c) { return c ? c->round : 0; }

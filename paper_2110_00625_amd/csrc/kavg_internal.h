@@ -55,6 +55,9 @@ struct LayerCall {
     int relu;              // forward: apply ReLU (hidden layer) / keep fp32 logits (last layer)
     void* scratch;         // fp32 forward: partial tiles of a split contraction (see f32_forward_plan)
     float lr;
+    // learner-level momentum: velocity of this layer's weights (learner 0; stride w_stride) and of its
+    // bias, null when off.  u <- beta u + g, w <- w - lr u.
+    float* u; float* ub; float beta;
 };
 
 // fp32 path

@@ -20,6 +20,7 @@ EXPORTS = [
     "kavg_set_data", "kavg_set_indices", "kavg_local_steps", "kavg_meta_update", "kavg_params",
     "kavg_momentum", "kavg_replica", "kavg_losses", "kavg_indices", "kavg_round", "kavg_last_error",
     "kavg_destroy", "kavg_meta_update_flat", "kavg_profile", "kavg_profile_read",
+    "kavg_velocity_bytes", "kavg_set_learner_momentum", "kavg_velocity",
 ]
 CLASS_NAMES = ["index", "forward", "loss", "backward", "update", "meta"]
 
@@ -68,6 +69,8 @@ def load_library():
         "kavg_losses": [c_vp, c_vp],
         "kavg_indices": [c_vp, c_vp],
         "kavg_destroy": [c_vp],
+        "kavg_set_learner_momentum": [c_vp, c_f, c_vp, c_sz],
+        "kavg_velocity": [c_vp, c_int, c_vp, c_sz],
         "kavg_profile": [c_vp, ctypes.c_uint, ctypes.c_uint],
         "kavg_profile_read": [c_vp, c_vp, c_vp],
         "kavg_meta_update_flat": [c_vp, c_vp, c_vp, c_sz, c_vp, c_sz, c_int, c_sz, c_f, c_vp],
@@ -75,6 +78,8 @@ def load_library():
         fn = getattr(lib, name)
         fn.restype = c_int
         fn.argtypes = args
+    lib.kavg_velocity_bytes.restype = c_sz
+    lib.kavg_velocity_bytes.argtypes = [c_vp]
     lib.kavg_round.restype = ctypes.c_uint64
     lib.kavg_round.argtypes = [c_vp]
     lib.kavg_last_error.restype = ctypes.c_char_p
@@ -174,6 +179,20 @@ class MAvg:
         assert idx_dev.numel() == self.P * self.K * self.B
         self._keep["idx"] = idx_dev
         _check(self.lib, self.ctx, self.lib.kavg_set_indices(self.ctx, idx_dev.data_ptr()))
+
+    def set_learner_momentum(self, beta):
+        """Heavy-ball momentum inside every learner (0 switches it off); allocates the velocity block."""
+        if beta == 0:
+            _check(self.lib, self.ctx, self.lib.kavg_set_learner_momentum(self.ctx, 0.0, None, 0))
+            self._keep.pop("vel", None)
+            return
+        nbytes = int(self.lib.kavg_velocity_bytes(self.ctx))
+        vel = self._torch.empty(nbytes, dtype=self._torch.uint8, device=self.device)
+        self._keep["vel"] = vel
+        _check(self.lib, self.ctx, self.lib.kavg_set_learner_momentum(self.ctx, float(beta), vel.data_ptr(), nbytes))
+
+    def velocity(self, j):
+        return self._out(self.lib.kavg_velocity, int(j))
 
     # -- the hot path -------------------------------------------------------
     def local_steps(self):

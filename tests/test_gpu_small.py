@@ -315,3 +315,49 @@ def test_profile_counts_launches(dims, fwd_per_step):
     assert g.profile_read()["update"][1] == 2                    # launches 0 and 4 of 6
     g.profile([])
     g.close()
+
+
+# ----------------------------------------------------------------- learner-level momentum
+@pytest.mark.parametrize("bf16", [False, True], ids=["fp32", "bf16"])
+@pytest.mark.parametrize("dims", [(200, 136, 72, 10), (136, 200, 24)], ids=["head_kernels", "generic_last_layer"])
+def test_learner_momentum_matches_oracle(bf16, dims):
+    P, K, B, lr, mu, beta = 3, 3, 40, 0.02, 0.9, 0.8
+    data = _dataset(600, dims, bf16, 101)
+    w0 = synth.he_normal_params(dims, 103)
+    g = kavg.MAvg(P, K, lr, mu, dims, B, kavg.KAVG_BF16 if bf16 else kavg.KAVG_FP32, index_seed=104)
+    X, y = _to_device(data, bf16)
+    g.set_data(X, y)
+    g.set_learner_momentum(beta)
+    g.set_params(w0)
+    o = O.MAvgOracle(P, K, lr, mu, dims, B, bf16=bf16, index_seed=104, learner_momentum=beta)
+    o.set_data(data["X32"], data["y"])
+    o.set_params(w0)
+    tol = TOL_BF16 if bf16 else TOL_FP32
+    for r in range(3):
+        g.local_steps()
+        o.local_steps()
+        for j in range(P):
+            assert worst_error(g.replica(j), o.replica(j), dims) < tol
+            assert worst_error(g.velocity(j), o.velocity(j), dims) < 10 * tol     # velocities persist across rounds
+        g.meta_update()
+        o.meta_update()
+        assert worst_error(g.params(), o.params(), dims) < tol
+    # the momentum run differs from the plain one (the check is not vacuous) ...
+    plain = O.MAvgOracle(P, K, lr, mu, dims, B, bf16=bf16, index_seed=104)
+    plain.set_data(data["X32"], data["y"])
+    plain.set_params(w0)
+    plain.local_steps()
+    o2 = O.MAvgOracle(P, K, lr, mu, dims, B, bf16=bf16, index_seed=104, learner_momentum=beta)
+    o2.set_data(data["X32"], data["y"])
+    o2.set_params(w0)
+    o2.local_steps()
+    assert worst_error(o2.replica(0), plain.replica(0), dims) > 5e-3
+    # ... and switching it off returns to Algorithm 1 as printed
+    g.set_learner_momentum(0.0)
+    g.set_params(w0)
+    g.local_steps()
+    assert worst_error(g.replica(0), plain.replica(0), dims) < tol
+    with pytest.raises(kavg.KavgError) as ei:
+        g.velocity(0)
+    assert ei.value.code == kavg.KAVG_ESTATE
+    g.close()

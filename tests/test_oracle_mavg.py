@@ -292,3 +292,78 @@ def test_planted_backprop_mistakes_are_caught(monkeypatch, mistake):
         monkeypatch.setattr(O, "backward", bad_backward)
     with pytest.raises(AssertionError):
         TM.test_backprop_three_layers_central_differences()
+
+
+# ---------------------------------------------------------------------------
+# learner-level momentum (Section 2: momentum "can also" be added at the learner level)
+# ---------------------------------------------------------------------------
+def _torch_momentum_sgd(w0, dims, X, y, batches, lr, beta):
+    """Library reference: torch.optim.SGD(momentum=beta) (heavy ball, no dampening, no Nesterov)."""
+    w = torch.tensor(w0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([w], lr=lr, momentum=beta)
+    L = len(dims) - 1
+    for ib in batches:
+        opt.zero_grad()
+        a = torch.tensor(X[ib], dtype=torch.float64)
+        o = 0
+        for l in range(1, L + 1):
+            W = w[o:o + dims[l] * dims[l - 1]].reshape(dims[l], dims[l - 1])
+            o += dims[l] * dims[l - 1]
+            b = w[o:o + dims[l]]
+            o += dims[l]
+            a = torch.nn.functional.linear(a, W, b)
+            if l < L:
+                a = torch.relu(a)
+        torch.nn.functional.cross_entropy(a, torch.tensor(y[ib], dtype=torch.long)).backward()
+        opt.step()
+    return w.detach().numpy()
+
+
+def test_learner_momentum_matches_library_heavy_ball():
+    # one learner, K steps, no meta momentum, ONE round: the replica is momentum SGD on its stream
+    K, B, lr, beta = 6, 5, 0.1, 0.8
+    X, y, w0 = _problem(DIMS, 100, 11)
+    o = O.MAvgOracle(1, K, lr, 0.0, DIMS, B, index_seed=5, learner_momentum=beta)
+    o.set_params(w0)
+    o.set_data(X, y)
+    o.local_steps()
+    want = _torch_momentum_sgd(w0, DIMS, X, y, [o.indices()[0, k] for k in range(K)], lr, beta)
+    assert np.max(np.abs(o.replica(0) - want)) < 1e-13
+    assert np.max(np.abs(want - _torch_sgd(w0, DIMS, X, y, [o.indices()[0, k] for k in range(K)], lr))) > 1e-3
+
+
+def test_learner_velocity_persists_across_rounds_and_is_per_learner():
+    P, K, B, lr, beta = 2, 2, 4, 0.1, 0.5
+    X, y, w0 = _problem(DIMS, 60, 12)
+    o = O.MAvgOracle(P, K, lr, 0.0, DIMS, B, index_seed=6, learner_momentum=beta)
+    o.set_params(w0)
+    o.set_data(X, y)
+    o.local_steps()
+    u_after_round1 = [o.velocity(j) for j in range(P)]
+    assert np.max(np.abs(u_after_round1[0] - u_after_round1[1])) > 1e-4          # own streams, own velocities
+    o.meta_update()
+    start = o.params()
+    o.local_steps()
+    # first step of round 2 for learner 0: u = beta*u_prev + g(start), w = start - lr*u
+    idx = o.indices()[0, 0]
+    _, g = O.minibatch_gradient(start, DIMS, X[idx], y[idx])
+    u1 = beta * u_after_round1[0] + g
+    w1 = start - lr * u1
+    idx = o.indices()[0, 1]
+    _, g2 = O.minibatch_gradient(w1, DIMS, X[idx], y[idx])
+    u2 = beta * u1 + g2
+    assert np.max(np.abs(o.velocity(0) - u2)) < 1e-14
+    assert np.max(np.abs(o.replica(0) - (w1 - lr * u2))) < 1e-14
+
+
+def test_learner_momentum_zero_is_algorithm_1():
+    X, y, w0 = _problem(DIMS, 60, 13)
+    a = O.MAvgOracle(3, 2, 0.1, 0.7, DIMS, 4, index_seed=7)
+    b = O.MAvgOracle(3, 2, 0.1, 0.7, DIMS, 4, index_seed=7, learner_momentum=0.0)
+    for o in (a, b):
+        o.set_params(w0)
+        o.set_data(X, y)
+        for _ in range(2):
+            o.local_steps()
+            o.meta_update()
+    assert np.array_equal(a.params(), b.params())
