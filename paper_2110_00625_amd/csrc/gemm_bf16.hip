@@ -201,7 +201,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
     constexpr int C_ELEMS = CTRANS ? BK * tpitch(TC) : TC * dpitch(BK);
     constexpr int OPER_BYTES = (R_ELEMS + C_ELEMS) * 2;
     constexpr int STAGE_BYTES = MODE == MODE_UPD ? 4 * 32 * SPITCH * 4 : 0;
-    constexpr int KRED_BYTES = (WK - 1) * WR * WC * MR * MC * 16 * 64 * 4;
+    constexpr int KRED_BYTES = WK > 1 ? WR * WC * MR * MC * 16 * 64 * 4 : 0;   // one k group's partial tiles
     constexpr int SMEM1 = OPER_BYTES > STAGE_BYTES ? OPER_BYTES : STAGE_BYTES;
     constexpr int SMEM_BYTES = SMEM1 > KRED_BYTES ? SMEM1 : KRED_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
@@ -310,7 +310,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
     }
 
     if (WK > 1) {
-        // sum the k groups' partial tiles into group 0, group by group (fixed order)
+        // sum the k groups' partial tiles into group 0, group by group (fixed order), through one LDS patch
         float* red = (float*)smem;
 #pragma unroll
         for (int g = 1; g < WK; ++g) {
@@ -321,20 +321,21 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                     for (int j = 0; j < MC; ++j)
 #pragma unroll
                         for (int e = 0; e < 16; ++e)
-                            red[(((g - 1) * WR * WC + wrc) * MR * MC * 16 + (i * MC + j) * 16 + e) * 64 + lane] = acc[i][j][e];
+                            red[((wrc * MR * MC + i * MC + j) * 16 + e) * 64 + lane] = acc[i][j][e];
             }
+            __syncthreads();
+            if (wk == 0) {
+#pragma unroll
+                for (int i = 0; i < MR; ++i)
+#pragma unroll
+                    for (int j = 0; j < MC; ++j)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            acc[i][j][e] += red[((wrc * MR * MC + i * MC + j) * 16 + e) * 64 + lane];
+            }
+            if (g + 1 < WK) __syncthreads();
         }
-        __syncthreads();
         if (wk != 0) return;
-#pragma unroll
-        for (int g = 1; g < WK; ++g)
-#pragma unroll
-            for (int i = 0; i < MR; ++i)
-#pragma unroll
-                for (int j = 0; j < MC; ++j)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        acc[i][j][e] += red[(((g - 1) * WR * WC + wrc) * MR * MC * 16 + (i * MC + j) * 16 + e) * 64 + lane];
     }
 
     // ---- epilogue: lane owns, per block, row r = l%32 and columns 8q + 4(l/32) + 0..3, q = 0..3
