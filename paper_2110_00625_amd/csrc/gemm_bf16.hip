@@ -36,10 +36,6 @@
 // required to be, the class count is padded in the logits / dZ_L buffers).
 #include "kavg_internal.h"
 
-#ifndef KAVG_TILE_OVERRIDE
-#define KAVG_TILE_OVERRIDE(t) (t)
-#endif
-
 namespace kavg {
 
 namespace {
@@ -56,7 +52,6 @@ struct Operand {
     const uint16_t* base;    // learner 0
     size_t lstride;          // elements between learners (0: shared by all learners)
     int ld;                  // elements between consecutive memory rows
-    int trans;               // 0: memory row = x, contiguous = k;  1: memory row = k, contiguous = x
     const int32_t* gather;   // optional: memory row = gather[row]
     long gstride;            // per learner
     int n_rows;              // valid memory rows (exact)
@@ -66,7 +61,7 @@ struct Operand {
 struct Args {
     Operand R, C;
     int nR, nC, nK;
-    int tiles_r, tiles_c, total_wg, chunk;       // workgroup -> tile map (see tile_of)
+    int tiles_r, tiles_c, total_wg, chunk;       // workgroup -> tile map (set by launch)
     // forward
     const float* bias; size_t bias_lstride;
     void* out; size_t out_lstride; int ld_out;   // bf16 activations or fp32 logits
@@ -472,28 +467,28 @@ hipError_t launch_tiled(const Args& a, int P, int tile, hipStream_t st) {
 
 hipError_t bf16_forward(const LayerCall& c, hipStream_t st) {
     Args a = {};
-    a.R = {(const uint16_t*)c.in, c.gather ? 0 : c.in_stride, c.ld_in, 0, c.gather, c.gather_stride, c.B, c.d_in};
-    a.C = {c.ws, c.ws_stride, c.d_in, 0, nullptr, 0, c.d_out, c.d_in};
+    a.R = {(const uint16_t*)c.in, c.gather ? 0 : c.in_stride, c.ld_in, c.gather, c.gather_stride, c.B, c.d_in};
+    a.C = {c.ws, c.ws_stride, c.d_in, nullptr, 0, c.d_out, c.d_in};
     a.nR = c.B; a.nC = c.d_out; a.nK = c.d_in;
     a.bias = c.b; a.bias_lstride = c.w_stride;
     a.out = c.out; a.out_lstride = c.out_stride; a.ld_out = c.ld_out; a.relu = c.relu;
-    return launch_tiled<MODE_FWD, false, false>(a, c.P, KAVG_TILE_OVERRIDE(pick_tile(MODE_FWD, a.nR, a.nC, c.P)), st);
+    return launch_tiled<MODE_FWD, false, false>(a, c.P, pick_tile(MODE_FWD, a.nR, a.nC, c.P), st);
 }
 
 hipError_t bf16_backward_data(const LayerCall& c, hipStream_t st) {
     Args a = {};
-    a.R = {(const uint16_t*)c.dz, c.dz_stride, c.ld_dz, 0, nullptr, 0, c.B, round8(c.d_out)};
-    a.C = {c.ws, c.ws_stride, c.d_in, 1, nullptr, 0, c.d_out, c.d_in};   // Cm(c, k) = W[k][c]
+    a.R = {(const uint16_t*)c.dz, c.dz_stride, c.ld_dz, nullptr, 0, c.B, round8(c.d_out)};
+    a.C = {c.ws, c.ws_stride, c.d_in, nullptr, 0, c.d_out, c.d_in};      // memory row = k: Cm(c, k) = W[k][c]
     a.nR = c.B; a.nC = c.d_in; a.nK = c.d_out;
     a.act_prev = (const uint16_t*)c.in; a.act_lstride = c.in_stride; a.ld_act = c.ld_in;
     a.out = c.dz_prev; a.out_lstride = c.dz_prev_stride; a.ld_out = c.ld_in;
-    return launch_tiled<MODE_BWD, false, true>(a, c.P, KAVG_TILE_OVERRIDE(pick_tile(MODE_BWD, a.nR, a.nC, c.P)), st);
+    return launch_tiled<MODE_BWD, false, true>(a, c.P, pick_tile(MODE_BWD, a.nR, a.nC, c.P), st);
 }
 
 hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     Args a = {};
-    a.R = {(const uint16_t*)c.dz, c.dz_stride, c.ld_dz, 1, nullptr, 0, c.B, c.ld_dz};      // R(r, k) = dZ[k][r]
-    a.C = {(const uint16_t*)c.in, c.gather ? 0 : c.in_stride, c.ld_in, 1, c.gather, c.gather_stride, c.B, c.d_in};
+    a.R = {(const uint16_t*)c.dz, c.dz_stride, c.ld_dz, nullptr, 0, c.B, c.ld_dz};         // memory row = k: R(r, k) = dZ[k][r]
+    a.C = {(const uint16_t*)c.in, c.gather ? 0 : c.in_stride, c.ld_in, c.gather, c.gather_stride, c.B, c.d_in};
     a.nR = c.d_out; a.nC = c.d_in; a.nK = c.B;
     a.w = c.w; a.w_lstride = c.w_stride; a.ws = c.ws; a.ws_lstride = c.ws_stride; a.b = c.b;
     a.lr = c.lr; a.u = c.u; a.ub = c.ub; a.beta = c.beta;

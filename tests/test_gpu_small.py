@@ -361,3 +361,26 @@ def test_learner_momentum_matches_oracle(bf16, dims):
         g.velocity(0)
     assert ei.value.code == kavg.KAVG_ESTATE
     g.close()
+
+
+# ----------------------------------------------------------------- K-AVG vs M-AVG sweep harness
+def test_sweep_harness_runs_and_is_consistent_with_the_oracle():
+    """The sweep only loops over configurations of the library; check its bookkeeping on a tiny
+    grid (non-power-of-two P) and one of its loss curves against the oracle."""
+    from paper_2110_00625_amd import sweep
+    dims, K, B, lr, rounds, N, seed = (40, 24, 5), 2, 8, 0.05, 4, 300, 7
+    out = sweep.sweep([3, 6], [0.0, 0.7], K=K, B=B, lr=lr, rounds=rounds, dims=dims, N=N, seed=seed, quiet=True)
+    assert len(out["runs"]) == 4 and all(len(r["curve"]) == rounds for r in out["runs"])
+    assert all(np.isfinite(r["final_loss"]) for r in out["runs"])
+    assert "| 3 |" in sweep.table(out) and "| 6 |" in sweep.table(out)
+    data = synth.make_dataset(N, dims[0], dims[-1], bf16=False, seed_data=seed, seed_teacher=seed + 1, teacher_hidden=64)
+    o = O.MAvgOracle(6, K, lr, 0.7, dims, B, index_seed=seed + 3)
+    o.set_data(data["X32"], data["y"])
+    o.set_params(synth.he_normal_params(dims, seed + 2))
+    want = []
+    for _ in range(rounds):
+        o.local_steps()
+        o.meta_update()
+        want.append(o.losses().mean())
+    got = [r for r in out["runs"] if r["P"] == 6 and r["mu"] == 0.7][0]["curve"]
+    assert np.max(np.abs(np.array(got) - np.array(want))) < 1e-4
