@@ -404,13 +404,13 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                     f32x4 step = g;
                     if (a.u) {                                  // heavy ball inside the learner
                         f32x4* up = (f32x4*)(a.u + (size_t)learner * a.w_lstride + (size_t)r * a.nC + c);
-                        step = a.beta * (*up) + g;
-                        *up = step;
+                        step = a.beta * __builtin_nontemporal_load(up) + g;
+                        __builtin_nontemporal_store(step, up);
                     }
                     w.x -= a.lr * step.x; w.y -= a.lr * step.y; w.z -= a.lr * step.z; w.w -= a.lr * step.w;
-                    *(f32x4*)(wbase + (size_t)r * a.nC + c) = w;
+                    __builtin_nontemporal_store(w, (f32x4*)(wbase + (size_t)r * a.nC + c));
                     u32x2 o = {pack2(w.x, w.y), pack2(w.z, w.w)};
-                    *(u32x2*)(sbase + (size_t)r * a.nC + c) = o;
+                    __builtin_nontemporal_store(o, (u32x2*)(sbase + (size_t)r * a.nC + c));
                 }
             }
         }
