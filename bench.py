@@ -51,9 +51,10 @@ def class_model(w, learner_momentum=False):
     for l in range(1, L + 1):
         wsz = d[l] * d[l - 1]
         ld_out = ldz if l == L else d[l]
-        if head and l == L:
-            by["update"] += P * ((8 + vel + (2 if bf else 0)) * wsz + (8 + vel) * d[l] + e * B * (ld_out + d[l - 1]))
-            fl["update"] += P * 2 * B * wsz
+        if head and l == L:     # both head kernels: A_{L-1} twice, W_L, dZ_L, dZ_{L-1}, master/shadow of W_L
+            by["head"] = P * (2 * e * B * d[l - 1] + e * wsz + 3 * e * B * ld_out + e * B * d[l - 1]
+                              + (8 + vel + (2 if bf else 0)) * wsz + (8 + vel) * d[l])
+            fl["head"] = P * 6 * B * wsz
             continue
         # forward: weights once, bias, input rows, output rows
         by["forward"] += P * (e * wsz + 4 * d[l] + e * B * d[l - 1] + (4 * B * ld_out if l == L else e * B * d[l]))
@@ -197,7 +198,7 @@ def main():
         del src, dst
 
     # warm-up rounds, every kernel class bracketed: gives the per-class breakdown
-    classes = ["index", "forward", "loss", "backward", "update", "meta"]
+    classes = ["index", "forward", "loss", "backward", "update", "meta", "head"]
     g.profile(classes)
     for _ in range(max(args.warmup, 1)):
         g.local_steps()
@@ -227,7 +228,7 @@ def main():
     per_round = w.K if heavy != "meta" else 1
     n_layers = len(w.dims) - 1
     head = w.dims[-1] <= 16
-    per_step = {"meta": 1, "update": n_layers, "forward": n_layers - (1 if head else 0),
+    per_step = {"meta": 1, "update": n_layers - (1 if head else 0), "forward": n_layers - (1 if head else 0),
                 "backward": n_layers - 1 - (1 if head else 0)}[heavy]
     launches = per_step * per_round * args.steps
     ms_heavy = ms_sampled / max(sampled, 1) * launches         # sampled mean launch time x all launches of the class

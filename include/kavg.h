@@ -162,7 +162,8 @@ int kavg_velocity(kavg_ctx* ctx, int j, float* out_host, size_t n);   /* u^j; KA
 #define KAVG_CLASS_BACKWARD 3   /* per-layer data gradients                */
 #define KAVG_CLASS_UPDATE   4   /* per-layer weight gradient + SGD update  */
 #define KAVG_CLASS_META     5   /* fused meta step                         */
-#define KAVG_NCLASS         6
+#define KAVG_CLASS_HEAD     6   /* last layer with <= 16 classes: forward + loss + data gradient, and its update */
+#define KAVG_NCLASS         7
 int kavg_profile(kavg_ctx* ctx, unsigned class_mask, unsigned every);
 int kavg_profile_read(kavg_ctx* ctx, double* ms_out, long long* launches_out);
 

@@ -352,7 +352,7 @@ int kavg_local_steps(kavg_ctx* c) {
         }
         if (head) {
             LayerCall q = layer_call(c, L, k);
-            Bracket br(c, KAVG_CLASS_LOSS);
+            Bracket br(c, KAVG_CLASS_HEAD);
             KAVG_HIP(c, head_forward_backward(q, c->y, idx_k, idx_ls, rowloss_k, bf ? 1 : 0, st));
         } else {
             Bracket br(c, KAVG_CLASS_LOSS);
@@ -362,7 +362,7 @@ int kavg_local_steps(kavg_ctx* c) {
         for (int l = L; l >= 1; --l) {                       // backward; W_l is read before it is updated
             LayerCall q = layer_call(c, l, k);
             if (head && l == L) {
-                Bracket br(c, KAVG_CLASS_UPDATE);
+                Bracket br(c, KAVG_CLASS_HEAD);
                 KAVG_HIP(c, head_update(q, idx_k, idx_ls, bf ? 1 : 0, st));
                 continue;
             }

@@ -22,7 +22,7 @@ EXPORTS = [
     "kavg_destroy", "kavg_meta_update_flat", "kavg_profile", "kavg_profile_read",
     "kavg_velocity_bytes", "kavg_set_learner_momentum", "kavg_velocity",
 ]
-CLASS_NAMES = ["index", "forward", "loss", "backward", "update", "meta"]
+CLASS_NAMES = ["index", "forward", "loss", "backward", "update", "meta", "head"]
 
 
 class KavgError(RuntimeError):

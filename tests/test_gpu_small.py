@@ -304,15 +304,16 @@ def test_mu_zero_is_plain_averaging():
 def test_profile_counts_launches(dims, fwd_per_step):
     # up to 16 classes the last layer's forward runs inside the loss kernel (one forward launch less)
     g, _o = _pair(2, 3, 0.1, 0.5, dims, 9, False, seed=97)
-    g.profile(["forward", "update", "meta"], every=1)
+    g.profile(["forward", "update", "meta", "head"], every=1)
     g.local_steps()
     g.meta_update()
     got = g.profile_read()
-    assert got["forward"][1] == 3 * fwd_per_step and got["update"][1] == 3 * 2 and got["meta"][1] == 1
+    assert got["forward"][1] == 3 * fwd_per_step and got["update"][1] == 3 * fwd_per_step and got["meta"][1] == 1
+    assert got["head"][1] == (3 * 2 if fwd_per_step == 1 else 0)
     assert got["backward"][1] == 0 and got["forward"][0] > 0.0
-    g.profile(["update"], every=4)
+    g.profile(["update"], every=2)
     g.local_steps()
-    assert g.profile_read()["update"][1] == 2                    # launches 0 and 4 of 6
+    assert g.profile_read()["update"][1] == (2 if fwd_per_step == 1 else 3)   # every second launch of 3 / 6
     g.profile([])
     g.close()
 
