@@ -2,11 +2,13 @@
 every learner walked by the oracle (minutes per round for the large ones, so
 this is a report script, not a collected test).
 
-  python tests/parity_report.py <workload> <rounds> [N] [--cpu-fp32]
+  python tests/parity_report.py <workload> <rounds> [N] [--cpu-fp32] [--resync]
 
 Prints, per learner, the replica error after the K local steps, and per round
 the per-tensor and worst relative error of the global model after the meta step.
 
+--resync starts every round of the GPU run from the oracle's state (global
+model, momentum buffer, round counter), so each line is the error of one round.
 --cpu-fp32 also walks a second CPU run whose only difference from the oracle
 is that its matrix products accumulate in fp32 (numpy float32 matmul on the
 same bf16-rounded operands) and prints how far THAT drifts from the oracle:
@@ -56,6 +58,7 @@ def main():
     import torch
     args = [a for a in sys.argv[1:] if not a.startswith("--")]
     cpu_fp32 = "--cpu-fp32" in sys.argv
+    resync = "--resync" in sys.argv
     name, rounds = args[0], int(args[1])
     w = WORKLOADS[name]
     N = int(args[2]) if len(args) > 2 else w.N
@@ -76,6 +79,8 @@ def main():
         o32.set_params(data["w0"])
     for r in range(rounds):
         t = time.time()
+        if resync:
+            g.set_state(o.params().astype(np.float32), o.momentum().astype(np.float32), r)
         g.local_steps()
         for j in range(w.P):                       # learner by learner, so progress is visible
             o.local_steps(learners=[j])

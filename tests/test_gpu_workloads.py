@@ -133,6 +133,29 @@ def _bf16_pair_K(w, N, K):
     return g, o
 
 
+def test_cifar_mlp_rounds_from_the_oracles_state():
+    """Every meta round started from the oracle's own state (global model, momentum buffer,
+    round counter handed to kavg_set_state): what one whole round -- K local steps of all 16
+    learners plus the meta step -- adds in error, without the round-over-round drift of two
+    free-running mixed-precision runs."""
+    w = CIFAR_MLP
+    g, o = _bf16_pair(w, w.N)
+    worst = 0.0
+    for r in range(5):
+        g.set_state(o.params().astype(np.float32), o.momentum().astype(np.float32), r)
+        g.local_steps()
+        o.local_steps()
+        assert np.array_equal(g.indices(), o.indices())
+        g.meta_update()
+        o.meta_update()
+        e = worst_error(g.params(), o.params(), w.dims)
+        ev = flat_error(g.momentum(), o.momentum())
+        worst = max(worst, e)
+        print("cifar_mlp round %d from the oracle's state: model %.3g, momentum buffer %.3g" % (r, e, ev))
+        assert e < 4e-3 and ev < 5e-2
+    g.close()
+
+
 @pytest.mark.parametrize("w,N,sample", [(NOISY_WIDE, 20000, (5, 31)), (LARGE, 20000, (0, 7))],
                          ids=["noisy_wide", "large"])
 def test_large_workloads_first_step_is_tight(w, N, sample):
