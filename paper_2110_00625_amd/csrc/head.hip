@@ -226,6 +226,7 @@ __global__ void __launch_bounds__(256) head_update_kernel(HeadArgs a) {
 #pragma unroll
         for (int e = 0; e < N; ++e) acc[c][e] = 0.f;
     }
+#pragma unroll 4
     for (int s = grp; s < a.B; s += 16) {
         const size_t arow = a.act_lstride ? (size_t)learner * a.act_lstride + (size_t)s * a.ld_act
                                           : (size_t)g[s] * a.ld_act;
