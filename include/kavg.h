@@ -167,6 +167,20 @@ int kavg_velocity(kavg_ctx* ctx, int j, float* out_host, size_t n);   /* u^j; KA
 int kavg_profile(kavg_ctx* ctx, unsigned class_mask, unsigned every);
 int kavg_profile_read(kavg_ctx* ctx, double* ms_out, long long* launches_out);
 
+/* Replay of the K local steps as one HIP graph (Algorithm 1, the inner loop
+ * over k: the launches of a round differ from those of the next only in the
+ * minibatch indices, which a kernel outside the graph writes first).  For
+ * launch-bound shapes (small layers, few learners) this removes most of the
+ * host's per-launch cost; results are bit-identical to the eager path, which
+ * stays the default.  With on != 0, kavg_local_steps runs eagerly once more
+ * (after kavg_init, kavg_set_data or kavg_set_learner_momentum), records the
+ * sequence on its next call and replays it from then on; calls made while
+ * kavg_profile has a non-zero mask run eagerly.  on == 0 waits for the stream
+ * and drops the recording.  KAVG_ESTATE: the context works on the default
+ * (null) stream, which cannot be captured.  While a call records, no other
+ * thread-unsafe HIP call may be made on this thread's behalf on that stream. */
+int kavg_graph(kavg_ctx* ctx, int on);
+
 uint64_t    kavg_round(const kavg_ctx* ctx);
 const char* kavg_last_error(const kavg_ctx* ctx);   /* ctx == NULL: text of the last failed kavg_init */
 int         kavg_destroy(kavg_ctx* ctx);            /* waits for the stream, frees the host context  */

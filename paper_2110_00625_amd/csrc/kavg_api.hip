@@ -113,6 +113,10 @@ struct kavg_ctx {
     size_t prof_used[KAVG_NCLASS];
     double prof_ms[KAVG_NCLASS];
     long long prof_launches[KAVG_NCLASS];
+    // replay of the K-step launch sequence as one HIP graph (kavg_graph)
+    bool graph_on = false;
+    bool warm = false;                  // the sequence has run eagerly once with the current pointers
+    hipGraphExec_t gexec = nullptr;
 
     float* w_tilde() const { return (float*)(ws + lo.off_w); }
     float* v() const { return (float*)(ws + lo.off_v); }
@@ -126,6 +130,8 @@ struct kavg_ctx {
 };
 
 namespace {
+
+void drop_graph(kavg_ctx* c);
 
 int fail(kavg_ctx* c, int code, const char* fmt, ...) {
     char* dst = c ? c->err : g_init_error;
@@ -311,6 +317,7 @@ int kavg_set_data(kavg_ctx* c, const void* X_dev, const int32_t* y_dev, int64_t 
     int rc = sync_and_check(c);
     if (rc != KAVG_OK) return rc == KAVG_EINVAL ? fail(c, KAVG_EINVAL, "a label lies outside [0, d_L)") : rc;
     c->X = X_dev; c->y = y_dev; c->N = N;
+    drop_graph(c);
     return KAVG_OK;
 }
 
@@ -320,24 +327,15 @@ int kavg_set_indices(kavg_ctx* c, const int32_t* idx_dev) {
     return KAVG_OK;
 }
 
-int kavg_local_steps(kavg_ctx* c) {
-    if (!c) return KAVG_EINVAL;
-    if (!c->have_params) return fail(c, KAVG_ESTATE, "no parameters: call kavg_set_params first");
-    if (!c->X) return fail(c, KAVG_ESTATE, "no data set: call kavg_set_data first");
-    if ((uint64_t)c->t0 + (uint64_t)c->K > ((uint64_t)1 << 24))
-        return fail(c, KAVG_ESTATE, "local step counter would exceed 2^24");
+namespace {
+
+// The K local steps of every learner after the indices are in place, and the per-step loss means.
+// All arguments are fixed between calls (workspace pointers, data pointers, shapes), which is what
+// lets kavg_local_steps replay this sequence as a graph.
+int issue_steps(kavg_ctx* c) {
     hipStream_t st = c->stream;
     const bool bf = c->dtype == KAVG_BF16;
     const int L = c->L;
-    {
-        Bracket br(c, KAVG_CLASS_INDEX);
-        if (c->user_idx)
-            KAVG_HIP(c, launch_index_import(c->idx(), c->user_idx, (size_t)c->P * c->K * c->B, (uint32_t)c->N,
-                                            c->flag(), st));
-        else
-            KAVG_HIP(c, launch_index_stream(c->idx(), c->P, c->K, c->B, c->seed, c->t0, (uint32_t)c->N, st));
-    }
-
     // With few classes the last layer runs as two dedicated kernels (forward + loss + data gradient,
     // then its update) instead of four generic launches.
     const bool head = head_supported(c->dims[L]);
@@ -377,6 +375,60 @@ int kavg_local_steps(kavg_ctx* c) {
     {
         Bracket br(c, KAVG_CLASS_LOSS);
         KAVG_HIP(c, launch_loss_mean(c->rowloss(), c->losses(), c->K * c->P, c->B, st));
+    }
+    {
+        Bracket br(c, KAVG_CLASS_LOSS);
+        KAVG_HIP(c, launch_loss_mean(c->rowloss(), c->losses(), c->K * c->P, c->B, st));
+    }
+    return KAVG_OK;
+}
+
+// forget the recorded sequence: its arguments (data, velocity buffer) are about to change
+void drop_graph(kavg_ctx* c) {
+    if (c->gexec) {
+        (void)hipStreamSynchronize(c->stream);           // it may still be running
+        (void)hipGraphExecDestroy(c->gexec);
+        c->gexec = nullptr;
+    }
+    c->warm = false;
+}
+
+}  // namespace
+
+int kavg_local_steps(kavg_ctx* c) {
+    if (!c) return KAVG_EINVAL;
+    if (!c->have_params) return fail(c, KAVG_ESTATE, "no parameters: call kavg_set_params first");
+    if (!c->X) return fail(c, KAVG_ESTATE, "no data set: call kavg_set_data first");
+    if ((uint64_t)c->t0 + (uint64_t)c->K > ((uint64_t)1 << 24))
+        return fail(c, KAVG_ESTATE, "local step counter would exceed 2^24");
+    hipStream_t st = c->stream;
+    {
+        Bracket br(c, KAVG_CLASS_INDEX);
+        if (c->user_idx)
+            KAVG_HIP(c, launch_index_import(c->idx(), c->user_idx, (size_t)c->P * c->K * c->B, (uint32_t)c->N,
+                                            c->flag(), st));
+        else
+            KAVG_HIP(c, launch_index_stream(c->idx(), c->P, c->K, c->B, c->seed, c->t0, (uint32_t)c->N, st));
+    }
+
+    // Everything after the indices has the same arguments in every round, so it can be replayed.
+    if (c->graph_on && c->warm && c->prof_mask == 0) {
+        if (!c->gexec) {
+            hipGraph_t g = nullptr;
+            KAVG_HIP(c, hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+            const int rc = issue_steps(c);
+            const hipError_t e = hipStreamEndCapture(st, &g);      // always ends the capture
+            if (rc != KAVG_OK) { if (g) (void)hipGraphDestroy(g); return rc; }
+            KAVG_HIP(c, e);
+            const hipError_t ei = hipGraphInstantiate(&c->gexec, g, nullptr, nullptr, 0);
+            (void)hipGraphDestroy(g);
+            if (ei != hipSuccess) { c->gexec = nullptr; KAVG_HIP(c, ei); }
+        }
+        KAVG_HIP(c, hipGraphLaunch(c->gexec, st));
+    } else {
+        const int rc = issue_steps(c);
+        if (rc != KAVG_OK) return rc;
+        c->warm = true;
     }
     c->t0 += (uint32_t)c->K;
     c->have_steps = true;
@@ -471,6 +523,18 @@ int kavg_profile_read(kavg_ctx* c, double* ms_out, long long* launches_out) {
     return KAVG_OK;
 }
 
+int kavg_graph(kavg_ctx* c, int on) {
+    if (!c) return KAVG_EINVAL;
+    if (on && c->stream == nullptr)
+        return fail(c, KAVG_ESTATE, "graph replay needs a stream of its own: the default stream cannot be captured");
+    if (!on) {
+        KAVG_HIP(c, hipStreamSynchronize(c->stream));
+        if (c->gexec) { (void)hipGraphExecDestroy(c->gexec); c->gexec = nullptr; }
+    }
+    c->graph_on = on != 0;
+    return KAVG_OK;
+}
+
 size_t kavg_velocity_bytes(const kavg_ctx* c) { return c ? (size_t)c->P * c->lo.stride * 4 : 0; }
 
 int kavg_set_learner_momentum(kavg_ctx* c, float beta, void* velocity_dev, size_t bytes) {
@@ -480,12 +544,14 @@ int kavg_set_learner_momentum(kavg_ctx* c, float beta, void* velocity_dev, size_
         if (beta != 0.f) return fail(c, KAVG_EINVAL, "beta > 0 needs a velocity buffer");
         KAVG_HIP(c, hipStreamSynchronize(c->stream));
         c->beta = 0.f; c->vel = nullptr;
+        drop_graph(c);
         return KAVG_OK;
     }
     if (((uintptr_t)velocity_dev % ALIGN) != 0) return fail(c, KAVG_EINVAL, "velocity buffer must be 256-byte aligned");
     if (bytes < kavg_velocity_bytes(c)) return fail(c, KAVG_ENOMEM, "velocity buffer has %zu bytes, %zu needed", bytes, kavg_velocity_bytes(c));
     KAVG_HIP(c, hipMemsetAsync(velocity_dev, 0, kavg_velocity_bytes(c), c->stream));
     c->beta = beta; c->vel = (float*)velocity_dev;
+    drop_graph(c);
     return KAVG_OK;
 }
 
@@ -505,6 +571,7 @@ const char* kavg_last_error(const kavg_ctx* c) { return c ? c->err : g_init_erro
 int kavg_destroy(kavg_ctx* c) {
     if (!c) return KAVG_EINVAL;
     hipError_t e = hipStreamSynchronize(c->stream);
+    if (c->gexec) (void)hipGraphExecDestroy(c->gexec);
     for (int k = 0; k < KAVG_NCLASS; ++k)
         for (hipEvent_t ev : c->prof_ev[k]) (void)hipEventDestroy(ev);
     delete c;

@@ -20,7 +20,7 @@ EXPORTS = [
     "kavg_set_data", "kavg_set_indices", "kavg_local_steps", "kavg_meta_update", "kavg_params",
     "kavg_momentum", "kavg_replica", "kavg_losses", "kavg_indices", "kavg_round", "kavg_last_error",
     "kavg_destroy", "kavg_meta_update_flat", "kavg_profile", "kavg_profile_read",
-    "kavg_velocity_bytes", "kavg_set_learner_momentum", "kavg_velocity",
+    "kavg_velocity_bytes", "kavg_set_learner_momentum", "kavg_velocity", "kavg_graph",
 ]
 CLASS_NAMES = ["index", "forward", "loss", "backward", "update", "meta", "head"]
 
@@ -73,6 +73,7 @@ def load_library():
         "kavg_velocity": [c_vp, c_int, c_vp, c_sz],
         "kavg_profile": [c_vp, ctypes.c_uint, ctypes.c_uint],
         "kavg_profile_read": [c_vp, c_vp, c_vp],
+        "kavg_graph": [c_vp, c_int],
         "kavg_meta_update_flat": [c_vp, c_vp, c_vp, c_sz, c_vp, c_sz, c_int, c_sz, c_f, c_vp],
     }.items():
         fn = getattr(lib, name)
@@ -232,6 +233,10 @@ class MAvg:
         for name in classes:
             mask |= 1 << CLASS_NAMES.index(name)
         _check(self.lib, self.ctx, self.lib.kavg_profile(self.ctx, mask, int(every)))
+
+    def graph(self, on=True):
+        """Replay the K local steps as one HIP graph (needs a non-default current stream at construction)."""
+        _check(self.lib, self.ctx, self.lib.kavg_graph(self.ctx, 1 if on else 0))
 
     def profile_read(self):
         """{class: (total ms, launches)} since the last profile() call."""

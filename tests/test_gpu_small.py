@@ -385,3 +385,80 @@ def test_sweep_harness_runs_and_is_consistent_with_the_oracle():
         want.append(o.losses().mean())
     got = [r for r in out["runs"] if r["P"] == 6 and r["mu"] == 0.7][0]["curve"]
     assert np.max(np.abs(np.array(got) - np.array(want))) < 1e-4
+
+
+# ----------------------------------------------------------------- graph replay of the K local steps
+GRAPH_CASES = [
+    ("fp32-head", (96, 72, 10), False, 3, 3, 20, 0.0),
+    ("bf16-head", (264, 200, 136, 10), True, 4, 2, 24, 0.0),
+    ("bf16-generic", (136, 72, 40), True, 3, 3, 16, 0.0),
+    ("bf16-learner-momentum", (264, 200, 10), True, 3, 2, 24, 0.8),
+]
+
+
+@pytest.mark.parametrize("tag,dims,bf16,P,K,B,beta", GRAPH_CASES, ids=[c[0] for c in GRAPH_CASES])
+def test_graph_replay_matches_the_eager_path_bit_for_bit(tag, dims, bf16, P, K, B, beta):
+    """The recorded sequence is replayed many times, with the program's own eager work and waits
+    between the replays (parameter read-backs, meta steps, a profiled round, a change of data set);
+    every round must leave exactly what the eager path leaves."""
+    torch = _torch()
+    dtype = kavg.KAVG_BF16 if bf16 else kavg.KAVG_FP32
+    data = _dataset(500, dims, bf16, 31)
+    data2 = _dataset(300, dims, bf16, 37)
+    w0 = synth.he_normal_params(dims, 33)
+    side = torch.cuda.Stream()
+    runs = []
+    for use_graph in (False, True):
+        with torch.cuda.stream(side):
+            g = kavg.MAvg(P, K, 0.05, 0.6, dims, B, dtype, index_seed=35)
+            X, y = _to_device(data, bf16)
+            X2, y2 = _to_device(data2, bf16)
+            torch.cuda.synchronize()
+            g.set_data(X, y)
+            if beta > 0:
+                g.set_learner_momentum(beta)
+            g.set_params(w0)
+            if use_graph:
+                g.graph(True)
+            trace = []
+            for r in range(9):
+                if r == 5:
+                    g.set_data(X2, y2)                  # the recording must be dropped and made again
+                if r == 7:
+                    g.profile(("forward", "update"))     # a profiled round runs eagerly
+                g.local_steps()
+                if r == 7:
+                    g.profile(())
+                reps = [g.replica(j) for j in range(P)]
+                losses = g.losses()
+                g.meta_update()
+                trace.append((g.indices(), reps, losses, g.params(), g.momentum()))
+            g.close()
+        runs.append(trace)
+    for r, (a, b) in enumerate(zip(*runs)):
+        assert np.array_equal(a[0], b[0]), "%s round %d: indices" % (tag, r)
+        for j in range(P):
+            assert np.array_equal(a[1][j], b[1][j]), "%s round %d: replica %d" % (tag, r, j)
+        assert np.array_equal(a[2], b[2]), "%s round %d: losses" % (tag, r)
+        assert np.array_equal(a[3], b[3]), "%s round %d: global model" % (tag, r)
+        assert np.array_equal(a[4], b[4]), "%s round %d: momentum" % (tag, r)
+
+
+def test_graph_replay_against_the_oracle():
+    torch = _torch()
+    dims = (96, 72, 10)
+    with torch.cuda.stream(torch.cuda.Stream()):
+        g, o = _pair(3, 3, 0.05, 0.5, dims, 20, False, 41)
+        g.graph(True)
+        _run_and_compare(g, o, dims, 5, TOL_FP32, "graph")
+        g.close()
+
+
+def test_graph_needs_a_stream_of_its_own():
+    g, _ = _pair(2, 2, 0.05, 0.5, (40, 24, 10), 8, False, 43)
+    with pytest.raises(kavg.KavgError) as e:
+        g.graph(True)
+    assert e.value.code == kavg.KAVG_ESTATE
+    g.local_steps()                                      # the context keeps working eagerly
+    g.graph(False)
+    g.close()
