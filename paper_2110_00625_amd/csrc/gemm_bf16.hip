@@ -298,6 +298,40 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
             }
     }
 
+    // What the epilogue reads from memory (bias of the lane's columns; ReLU mask of its outputs) is
+    // requested here, ahead of the contraction, so that its latency is not paid after the last slice.
+    // Only the wavefronts of k group 0 reach the epilogue.
+    f32x4 ebias[MODE == MODE_FWD ? MC : 1][4];
+    u32x2 emask[MODE == MODE_BWD ? MR : 1][MODE == MODE_BWD ? MC : 1][4];
+    if (MODE == MODE_FWD && wk == 0) {
+        const float* bias = a.bias + (size_t)learner * a.bias_lstride;
+#pragma unroll
+        for (int j = 0; j < MC; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = c0 + (wc * MC + j) * 32 + q * 8 + (lane >> 5) * 4;
+                ebias[j][q].x = c + 0 < a.nC ? bias[c + 0] : 0.f;
+                ebias[j][q].y = c + 1 < a.nC ? bias[c + 1] : 0.f;
+                ebias[j][q].z = c + 2 < a.nC ? bias[c + 2] : 0.f;
+                ebias[j][q].w = c + 3 < a.nC ? bias[c + 3] : 0.f;
+            }
+    }
+    if (MODE == MODE_BWD && wk == 0) {
+#pragma unroll
+        for (int i = 0; i < MR; ++i) {
+            const int r = r0 + (wr * MR + i) * 32 + (lane & 31);
+#pragma unroll
+            for (int j = 0; j < MC; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int c = c0 + (wc * MC + j) * 32 + q * 8 + (lane >> 5) * 4;
+                    emask[i][j][q] = (u32x2){0u, 0u};
+                    if (r < a.nR && c < a.nC)
+                        emask[i][j][q] = *(const u32x2*)(a.act_prev + (size_t)learner * a.act_lstride + (size_t)r * a.ld_act + c);
+                }
+        }
+    }
+
     fetch(0);
     if (!DB) {
         for (int k0 = 0; k0 < a.nK; k0 += BK) {
@@ -371,11 +405,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                     float v2 = acc[i][j][4 * q + 2], v3 = acc[i][j][4 * q + 3];
                     if (MODE == MODE_FWD) {
                         if (c >= a.ld_out) continue;
-                        const float* bias = a.bias + (size_t)learner * a.bias_lstride;
-                        v0 += c + 0 < a.nC ? bias[c + 0] : 0.f;
-                        v1 += c + 1 < a.nC ? bias[c + 1] : 0.f;
-                        v2 += c + 2 < a.nC ? bias[c + 2] : 0.f;
-                        v3 += c + 3 < a.nC ? bias[c + 3] : 0.f;
+                        v0 += ebias[j][q].x; v1 += ebias[j][q].y; v2 += ebias[j][q].z; v3 += ebias[j][q].w;
                         if (a.relu) {
                             u32x2 o = {pack2(fmaxf(v0, 0.f), fmaxf(v1, 0.f)), pack2(fmaxf(v2, 0.f), fmaxf(v3, 0.f))};
                             *(u32x2*)((uint16_t*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
@@ -385,7 +415,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                         }
                     } else {
                         if (c >= a.nC) continue;
-                        const u32x2 m = *(const u32x2*)(a.act_prev + (size_t)learner * a.act_lstride + (size_t)r * a.ld_act + c);
+                        const u32x2 m = emask[i][j][q];
                         // stored activations are relu outputs (never negative): positive <=> non-zero magnitude
                         v0 = (m.x & 0x7FFFu) ? v0 : 0.f;
                         v1 = (m.x & 0x7FFF0000u) ? v1 : 0.f;
