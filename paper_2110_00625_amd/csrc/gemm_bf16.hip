@@ -47,6 +47,10 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 enum { MODE_FWD = 0, MODE_BWD = 1, MODE_UPD = 2 };
+// Main-loop pipelines.  PLAIN: one LDS buffer, the next slice waits in registers.  LDS2: two LDS
+// buffers, the next slice is written while the current one is read.  DMA: two LDS buffers filled by
+// direct global->LDS loads (no registers, no LDS store instructions); k-contiguous operands only.
+enum { PIPE_PLAIN = 0, PIPE_LDS2 = 1, PIPE_DMA = 2 };
 
 struct Operand {
     const uint16_t* base;    // learner 0
@@ -177,15 +181,75 @@ __device__ __forceinline__ bf16x8 frag_trans(const uint16_t* tile, int block_x0,
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// Direct global -> LDS loads (global_load_lds_dwordx4): a wavefront instruction moves 64 pieces of
+// 16 bytes into 1 KB of consecutive LDS, lane l to byte 16*l, so rows cannot be padded.  The tile
+// is [x][BK] with rows of exactly BK bf16 and the 16-byte chunks of row x permuted by an XOR:
+// LDS slot (x, c') holds memory chunk c' ^ (x mod 16) (rows of 256 bytes, BK = 128).  Sixteen
+// consecutive rows then put any one chunk index into sixteen different 16-byte bank groups, so
+// fragment reads are conflict-free.  (Rows of 128 bytes with (x/2) mod 8 and three or four LDS
+// buffers were measured too: no faster.)  Piece i of a wavefront covers slots (wave*N + i)*64 .. +63.
+// Rows outside the operand are clamped to its last row: they only reach outputs that are never
+// stored.  A chunk beyond the contraction length is clamped too and zeroed in LDS after it has
+// landed (fix_tail), by the lane that loaded it.
+template <int BK> __device__ __forceinline__ int dma_swizzle(int x) {
+    static_assert(BK == 128, "rows of 256 bytes: one row per bank period");
+    return x & 15;
+}
+
+template <int X, int BK, int NT>
+struct DmaLoader {
+    static constexpr int N = X * BK / 8 / NT;
+    static constexpr int CPR = BK / 8;           // chunks per row
+    const uint16_t* row[N];      // start of the (clamped) memory row of piece i
+    int chunk[N];                // memory chunk (of 8 bf16) within the slice
+    __device__ __forceinline__ void init(const Operand& o, const uint16_t* base, const int32_t* gather, int x0, int tid) {
+        const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int slot = (wave * N + i) * 64 + lane;
+            const int xr = slot / CPR;
+            const int x = min(x0 + xr, o.n_rows - 1);
+            chunk[i] = (slot % CPR) ^ dma_swizzle<BK>(xr);
+            row[i] = base + (gather ? (long)gather[x] : (long)x) * o.ld;
+        }
+    }
+    __device__ __forceinline__ void load(const Operand& o, int k0, uint16_t* tile, int tid) const {
+        typedef __attribute__((address_space(3))) void* lds_p;
+        typedef const __attribute__((address_space(1))) void* glb_p;
+        const int wave = tid >> 6;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int k = min(k0 + chunk[i] * 8, o.n_cont - 8);
+            __builtin_amdgcn_global_load_lds((glb_p)(row[i] + k), (lds_p)(tile + (wave * N + i) * 64 * 8), 16, 0, 0);
+        }
+    }
+    __device__ __forceinline__ void fix_tail(const Operand& o, int k0, uint16_t* tile, int tid) const {
+        const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+            if (k0 + chunk[i] * 8 >= o.n_cont) {
+                const u32x4 zero = {0u, 0u, 0u, 0u};
+                *(u32x4*)(tile + ((wave * N + i) * 64 + lane) * 8) = zero;
+            }
+    }
+};
+
+template <int BK>
+__device__ __forceinline__ bf16x8 frag_swizzled(const uint16_t* tile, int block_row0, int kk, int lane) {
+    const int x = block_row0 + (lane & 31);
+    const int c = (kk * 2 + (lane >> 5)) ^ dma_swizzle<BK>(x);
+    return *(const bf16x8*)(tile + x * BK + c * 8);
+}
+
 // LDS budget of a kernel shape (shared by the kernel and its launcher).
-template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RTRANS, bool CTRANS, bool DB>
+template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RTRANS, bool CTRANS, int PIPE>
 struct Shape {
     static constexpr int MR = TR / (32 * WR), MC = TC / (32 * WC);
     static constexpr int WTC = MC * 32;                 // columns of a wavefront's tile
     static constexpr int SPITCH = WTC + 4;              // update epilogue: fp32 staging row, padded
-    static constexpr int R_ELEMS = RTRANS ? BK * tpitch(TR) : TR * dpitch(BK);
-    static constexpr int C_ELEMS = CTRANS ? BK * tpitch(TC) : TC * dpitch(BK);
-    static constexpr int OPER_BYTES = (DB ? 2 : 1) * (R_ELEMS + C_ELEMS) * 2;
+    static constexpr int R_ELEMS = PIPE == PIPE_DMA ? TR * BK : RTRANS ? BK * tpitch(TR) : TR * dpitch(BK);
+    static constexpr int C_ELEMS = PIPE == PIPE_DMA ? TC * BK : CTRANS ? BK * tpitch(TC) : TC * dpitch(BK);
+    static constexpr int OPER_BYTES = (PIPE == PIPE_PLAIN ? 1 : 2) * (R_ELEMS + C_ELEMS) * 2;
     static constexpr int STAGE_BYTES = MODE == MODE_UPD ? 4 * 32 * SPITCH * 4 : 0;
     static constexpr int KRED_BYTES = WK > 1 ? WR * WC * MR * MC * 16 * 64 * 4 : 0;   // one k group's partial tiles
     static constexpr int SMEM1 = OPER_BYTES > STAGE_BYTES ? OPER_BYTES : STAGE_BYTES;
@@ -196,17 +260,17 @@ struct Shape {
 // TR x TC output tile; WR x WC x WK wavefronts: WR x WC of them tile the output, each owning MR x MC
 // MFMA blocks of 32x32, and WK groups of those split every slice along k (their partial tiles are
 // summed through LDS at the end, in fixed order).  BK = slice length.  One slice is always in
-// flight in registers ahead of the one being multiplied; with DB the LDS tiles are double-buffered,
+// flight in registers ahead of the one being multiplied; with PIPE_LDS2 the LDS tiles are double-buffered,
 // so the next slice is written while the current one is read and a slice costs one barrier, not two.
-template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RTRANS, bool CTRANS, bool DB>
+template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RTRANS, bool CTRANS, int PIPE>
 __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
     constexpr int NW = WR * WC * WK, NT = 64 * NW;
     constexpr int MR = TR / (32 * WR), MC = TC / (32 * WC);
     static_assert(MR >= 1 && MC >= 1, "tile too small for the wave grid");
     static_assert((BK / 16) % WK == 0, "slice must split evenly over the k groups");
-    static_assert(MODE != MODE_UPD || (WK == 1 && NW == 4 && !DB), "the update epilogue assumes 4 wavefronts, no k split, one LDS buffer");
+    static_assert(MODE != MODE_UPD || (WK == 1 && NW == 4 && PIPE == PIPE_PLAIN), "the update epilogue assumes 4 wavefronts, no k split, one LDS buffer");
     static_assert(NT % (TR / 8) == 0 && NT % (TC / 8) == 0, "loader column mapping");
-    typedef Shape<MODE, TR, TC, WR, WC, WK, BK, RTRANS, CTRANS, DB> SH;
+    typedef Shape<MODE, TR, TC, WR, WC, WK, BK, RTRANS, CTRANS, PIPE> SH;
     constexpr int WTC = SH::WTC, SPITCH = SH::SPITCH, R_ELEMS = SH::R_ELEMS, C_ELEMS = SH::C_ELEMS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];     // SH::SMEM_BYTES, set at launch
     uint16_t* Rs = (uint16_t*)smem;                 // buffer b: Rs + b*(R_ELEMS + C_ELEMS), Cs likewise
@@ -265,12 +329,14 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
             bf16x8 cf[MC], rf[MR];
 #pragma unroll
             for (int j = 0; j < MC; ++j)
-                cf[j] = CTRANS ? frag_trans<TC>(C, (wc * MC + j) * 32, kk, lane)
-                               : frag_direct<BK>(C, (wc * MC + j) * 32, kk, lane);
+                if constexpr (PIPE == PIPE_DMA) cf[j] = frag_swizzled<BK>(C, (wc * MC + j) * 32, kk, lane);
+                else cf[j] = CTRANS ? frag_trans<TC>(C, (wc * MC + j) * 32, kk, lane)
+                                    : frag_direct<BK>(C, (wc * MC + j) * 32, kk, lane);
 #pragma unroll
             for (int i = 0; i < MR; ++i)
-                rf[i] = RTRANS ? frag_trans<TR>(R, (wr * MR + i) * 32, kk, lane)
-                               : frag_direct<BK>(R, (wr * MR + i) * 32, kk, lane);
+                if constexpr (PIPE == PIPE_DMA) rf[i] = frag_swizzled<BK>(R, (wr * MR + i) * 32, kk, lane);
+                else rf[i] = RTRANS ? frag_trans<TR>(R, (wr * MR + i) * 32, kk, lane)
+                                    : frag_direct<BK>(R, (wr * MR + i) * 32, kk, lane);
 #pragma unroll
             for (int i = 0; i < MR; ++i)
 #pragma unroll
@@ -332,8 +398,31 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
         }
     }
 
+    if constexpr (PIPE == PIPE_DMA) {
+        static_assert(!RTRANS && !CTRANS && MODE != MODE_UPD, "direct LDS loads: k-contiguous operands only");
+        DmaLoader<TR, BK, NT> rdma; DmaLoader<TC, BK, NT> cdma;
+        rdma.init(a.R, Rbase, Rg, r0, tid);
+        cdma.init(a.C, Cbase, Cg, c0, tid);
+        rdma.load(a.R, 0, Rs, tid);
+        cdma.load(a.C, 0, Cs, tid);
+        int buf = 0;
+        for (int k0 = 0; k0 < a.nK; k0 += BK, buf ^= 1) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0): this wavefront's part of slice k0 is in LDS
+            if (k0 + BK > a.R.n_cont || k0 + BK > a.C.n_cont) {      // ragged end of the contraction
+                rdma.fix_tail(a.R, k0, Rs + buf * BUF_ELEMS, tid);
+                cdma.fix_tail(a.C, k0, Cs + buf * BUF_ELEMS, tid);
+            }
+            __syncthreads();                            // everyone's part is; the other buffer is no longer read
+            if (k0 + BK < a.nK) {                       // next slice lands while this one is multiplied
+                rdma.load(a.R, k0 + BK, Rs + (buf ^ 1) * BUF_ELEMS, tid);
+                cdma.load(a.C, k0 + BK, Cs + (buf ^ 1) * BUF_ELEMS, tid);
+            }
+            multiply(buf);
+        }
+        __syncthreads();                                // tiles are dead: the k-group reduction reuses their LDS
+    } else {
     fetch(0);
-    if (!DB) {
+    if (PIPE == PIPE_PLAIN) {
         for (int k0 = 0; k0 < a.nK; k0 += BK) {
             stash(0);
             __syncthreads();
@@ -359,6 +448,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
             multiply(buf);
             __syncthreads();
         }
+    }
     }
 
     if (WK > 1) {
@@ -463,7 +553,9 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                     w.x -= a.lr * step.x; w.y -= a.lr * step.y; w.z -= a.lr * step.z; w.w -= a.lr * step.w;
                     __builtin_nontemporal_store(w, (f32x4*)(wbase + (size_t)r * a.nC + c));
                     u32x2 o = {pack2(w.x, w.y), pack2(w.z, w.w)};
-                    __builtin_nontemporal_store(o, (u32x2*)(sbase + (size_t)r * a.nC + c));
+                    // the shadow is what the next forward pass reads: an ordinary store leaves it in the
+                    // memory-side cache (the master and the velocity, streamed once per step, bypass it)
+                    *(u32x2*)(sbase + (size_t)r * a.nC + c) = o;
                 }
             }
         }
@@ -475,22 +567,22 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
     }
 }
 
-template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RT, bool CT, bool DB>
+template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RT, bool CT, int PIPE>
 hipError_t launch(Args a, int P, hipStream_t st) {
     a.tiles_c = (a.nC + TC - 1) / TC;
     a.tiles_r = (a.nR + TR - 1) / TR;
     a.total_wg = a.tiles_c * a.tiles_r * P;
     a.chunk = (a.total_wg + 7) / 8;
     dim3 grid(8 * a.chunk);
-    constexpr int SMEM = Shape<MODE, TR, TC, WR, WC, WK, BK, RT, CT, DB>::SMEM_BYTES;
+    constexpr int SMEM = Shape<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE>::SMEM_BYTES;
     static_assert(SMEM <= 160 * 1024, "more LDS than a compute unit has");
     if (SMEM > 64 * 1024) {                     // beyond the default limit: raise it once for this kernel
         static hipError_t raised = hipFuncSetAttribute(
-            (const void*)gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, DB>,
+            (const void*)gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE>,
             hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
         if (raised != hipSuccess) return raised;
     }
-    hipLaunchKernelGGL((gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, DB>), grid, dim3(64 * WR * WC * WK),
+    hipLaunchKernelGGL((gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE>), grid, dim3(64 * WR * WC * WK),
                        SMEM, st, a);
     return hipGetLastError();
 }
@@ -517,14 +609,15 @@ int pick_tile(int mode, int nR, int nC, int P) {
 template <int MODE, bool RT, bool CT>
 hipError_t launch_tiled(const Args& a, int P, int tile, hipStream_t st) {
     switch (tile) {
-        case T128x128: return launch<MODE, 128, 128, 2, 2, 1, 64, RT, CT, false>(a, P, st);
-        case T128x64:  return launch<MODE, 128, 64, 2, 2, 1, 64, RT, CT, false>(a, P, st);
-        case T64x128:  return launch<MODE, 64, 128, 2, 2, 1, 64, RT, CT, false>(a, P, st);
+        case T128x128: return launch<MODE, 128, 128, 2, 2, 1, 64, RT, CT, PIPE_PLAIN>(a, P, st);
+        case T128x64:  return launch<MODE, 128, 64, 2, 2, 1, 64, RT, CT, PIPE_PLAIN>(a, P, st);
+        case T64x128:  return launch<MODE, 64, 128, 2, 2, 1, 64, RT, CT, PIPE_PLAIN>(a, P, st);
         default:
-            // forward: slices of 128, one LDS buffer; backward-data (weights read through the transpose
-            // path) measured ~10 % faster with slices of 64 and double-buffered LDS
-            if (MODE == MODE_BWD) return launch<MODE, 64, 64, 2, 2, 2, 64, RT, CT, true>(a, P, st);
-            return launch<MODE, 64, 64, 2, 2, 2, 128, RT, CT, false>(a, P, st);
+            // forward: slices of 128 loaded straight into LDS (measured 26 against 30 us for layer 1 of the
+            // CIFAR-MLP workload); backward-data (weights read through the transpose path): slices of 64,
+            // double-buffered LDS filled from registers
+            if constexpr (MODE == MODE_FWD) return launch<MODE, 64, 64, 2, 2, 2, 128, RT, CT, PIPE_DMA>(a, P, st);
+            else return launch<MODE, 64, 64, 2, 2, 2, 64, RT, CT, PIPE_LDS2>(a, P, st);
     }
 }
 
@@ -557,7 +650,7 @@ hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     a.nR = c.d_out; a.nC = c.d_in; a.nK = c.B;
     a.w = c.w; a.w_lstride = c.w_stride; a.ws = c.ws; a.ws_lstride = c.ws_stride; a.b = c.b;
     a.lr = c.lr; a.u = c.u; a.ub = c.ub; a.beta = c.beta;
-    return launch<MODE_UPD, 128, 128, 2, 2, 1, 64, true, true, false>(a, c.P, st);
+    return launch<MODE_UPD, 128, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN>(a, c.P, st);
 }
 
 }  // namespace kavg

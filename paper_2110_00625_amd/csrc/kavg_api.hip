@@ -376,10 +376,6 @@ int issue_steps(kavg_ctx* c) {
         Bracket br(c, KAVG_CLASS_LOSS);
         KAVG_HIP(c, launch_loss_mean(c->rowloss(), c->losses(), c->K * c->P, c->B, st));
     }
-    {
-        Bracket br(c, KAVG_CLASS_LOSS);
-        KAVG_HIP(c, launch_loss_mean(c->rowloss(), c->losses(), c->K * c->P, c->B, st));
-    }
     return KAVG_OK;
 }
 

@@ -71,7 +71,9 @@ meta_update_vec_kernel(float* __restrict__ w_tilde, float* __restrict__ v, float
             u16x4 h = {to_bf16_bits(wn.x), to_bf16_bits(wn.y), to_bf16_bits(wn.z), to_bf16_bits(wn.w)};
             u16x4* so = (u16x4*)shadow + i;
             const size_t ss4 = sstride / 4;
-            for (int jj = 0; jj < P; ++jj) __builtin_nontemporal_store(h, so + (size_t)jj * ss4);
+            // ordinary stores: the shadows are what the next forward pass reads, so they may stay in
+            // the memory-side cache (the replicas above, read again only by the updates, bypass it)
+            for (int jj = 0; jj < P; ++jj) so[(size_t)jj * ss4] = h;
         }
     } else {
         const size_t e = 4 * n4 + (i - n4);               // ragged tail: at most 3 parameters
