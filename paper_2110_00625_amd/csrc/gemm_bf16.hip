@@ -76,6 +76,7 @@ struct Args {
     float* w; size_t w_lstride; uint16_t* ws; size_t ws_lstride; float* b;
     float lr;
     float* u; float* ub; float beta;             // velocities of weights / bias (stride w_lstride), null: plain SGD
+    const int32_t* next_gather;                  // rows of C's data set that the next step gathers (stride C.gstride), or null
 };
 
 __device__ __forceinline__ uint16_t bf16_bits(float x) {
@@ -311,6 +312,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
     StageRegs<TR * BK / 8 / NT> rg;
     StageRegs<TC * BK / 8 / NT> cg;
     float bias_sum = 0.f;                       // update: column sum of dZ for row r0 + tid
+    uint32_t touched = 0;                       // update of the first layer: see the prefetch below
 
     auto fetch = [&](int k0) {
         if (RTRANS) rtl.load(rg, a.R, k0, tid); else rdl.load(rg, a.R, k0);
@@ -422,6 +424,26 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
         __syncthreads();                                // tiles are dead: the k-group reduction reuses their LDS
     } else {
     fetch(0);
+    // Update of the first layer: the rows that the next local step samples are scattered over the data
+    // set, and its forward pass, with one slice of look-ahead, would pay the latency of such a read
+    // in every slice.  This launch is bound by its parameter stream and lasts long, so its
+    // workgroups touch those rows, one 128-byte line per lane (the learner's rows are spread over
+    // the learner's workgroups, which run on the XCD that will run its forward tiles).  The
+    // value is only kept alive until the end of the kernel.
+    if (MODE == MODE_UPD && a.next_gather) {
+        const int lines_per_row = (a.C.n_cont * 2 + 127) / 128;
+        const int lines = a.C.n_rows * lines_per_row;                 // of this learner
+        const int wgs = a.tiles_r * a.tiles_c;
+        const int per_wg = (lines + wgs - 1) / wgs;
+        const int32_t* ng = a.next_gather + (long)learner * a.C.gstride;
+        for (int t = tid; t < per_wg; t += NT) {
+            const int line = tile * per_wg + t;
+            if (line < lines) {
+                const int row = line / lines_per_row, ln = line - row * lines_per_row;
+                touched ^= *(const uint32_t*)(a.C.base + (long)ng[row] * a.C.ld + ln * 64);
+            }
+        }
+    }
     if (PIPE == PIPE_PLAIN) {
         for (int k0 = 0; k0 < a.nK; k0 += BK) {
             stash(0);
@@ -564,6 +586,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
             if (a.ub) { bias_sum = a.beta * a.ub[at] + bias_sum; a.ub[at] = bias_sum; }
             a.b[at] = a.b[at] - a.lr * bias_sum;
         }
+        asm volatile("" :: "v"(touched));               // the touched lines' loads are not dead code
     }
 }
 
@@ -650,6 +673,7 @@ hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     a.nR = c.d_out; a.nC = c.d_in; a.nK = c.B;
     a.w = c.w; a.w_lstride = c.w_stride; a.ws = c.ws; a.ws_lstride = c.ws_stride; a.b = c.b;
     a.lr = c.lr; a.u = c.u; a.ub = c.ub; a.beta = c.beta;
+    a.next_gather = c.gather ? c.next_gather : nullptr;
     return launch<MODE_UPD, 128, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN>(a, c.P, st);
 }
 

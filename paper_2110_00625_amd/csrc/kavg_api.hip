@@ -210,6 +210,7 @@ LayerCall layer_call(const kavg_ctx* c, int l /*1..L*/, int k) {
     if (l == 1) {
         q.in = c->X; q.ld_in = c->dims[0]; q.in_stride = 0;
         q.gather = c->idx() + (size_t)k * c->B; q.gather_stride = (long)c->K * c->B;
+        q.next_gather = k + 1 < c->K ? q.gather + c->B : nullptr;
     } else {
         q.in = c->ws + lo.off_act[l - 2]; q.ld_in = c->dims[l - 1]; q.in_stride = (size_t)c->B * q.ld_in;
         q.dz_prev = c->ws + lo.off_dz[l - 2]; q.dz_prev_stride = (size_t)c->B * q.ld_in;

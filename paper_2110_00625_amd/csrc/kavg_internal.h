@@ -46,6 +46,9 @@ struct LayerCall {
     // activations entering the layer: [P][B][ld_in]; or, with gather != null, rows X[gather[j][m]]
     const void* in; int ld_in; size_t in_stride;
     const int32_t* gather; long gather_stride;
+    // update of the first layer only: rows the NEXT local step will gather (same layout as gather),
+    // or null.  The kernel touches them so that the next forward pass finds them in cache.
+    const int32_t* next_gather;
     // activations leaving the layer / logits: [P][B][ld_out]
     void* out; int ld_out; size_t out_stride;
     // gradient w.r.t. this layer's pre-activation: [P][B][ld_dz]
