@@ -263,7 +263,7 @@ struct Shape {
 // summed through LDS at the end, in fixed order).  BK = slice length.  One slice is always in
 // flight in registers ahead of the one being multiplied; with PIPE_LDS2 the LDS tiles are double-buffered,
 // so the next slice is written while the current one is read and a slice costs one barrier, not two.
-template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RTRANS, bool CTRANS, int PIPE>
+template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RTRANS, bool CTRANS, int PIPE, bool SHADOW_CACHED = false>
 __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
     constexpr int NW = WR * WC * WK, NT = 64 * NW;
     constexpr int MR = TR / (32 * WR), MC = TC / (32 * WC);
@@ -367,36 +367,35 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
     }
 
     // What the epilogue reads from memory (bias of the lane's columns; ReLU mask of its outputs) is
-    // requested here, ahead of the contraction, so that its latency is not paid after the last slice.
+    // requested here, ahead of the contraction, so that its latency is not paid after the last slice
+    // -- for single-block wavefront tiles only: with more blocks the extra registers cost occupancy.
     // Only the wavefronts of k group 0 reach the epilogue.
-    f32x4 ebias[MODE == MODE_FWD ? MC : 1][4];
-    u32x2 emask[MODE == MODE_BWD ? MR : 1][MODE == MODE_BWD ? MC : 1][4];
-    if (MODE == MODE_FWD && wk == 0) {
+    constexpr bool EARLY = MR * MC == 1;
+    auto bias_of = [&](int j, int q) {
         const float* bias = a.bias + (size_t)learner * a.bias_lstride;
+        const int c = c0 + (wc * MC + j) * 32 + q * 8 + (lane >> 5) * 4;
+        f32x4 b;
+        b.x = c + 0 < a.nC ? bias[c + 0] : 0.f;
+        b.y = c + 1 < a.nC ? bias[c + 1] : 0.f;
+        b.z = c + 2 < a.nC ? bias[c + 2] : 0.f;
+        b.w = c + 3 < a.nC ? bias[c + 3] : 0.f;
+        return b;
+    };
+    auto mask_of = [&](int i, int j, int q) {
+        const int r = r0 + (wr * MR + i) * 32 + (lane & 31);
+        const int c = c0 + (wc * MC + j) * 32 + q * 8 + (lane >> 5) * 4;
+        u32x2 m = {0u, 0u};
+        if (r < a.nR && c < a.nC)
+            m = *(const u32x2*)(a.act_prev + (size_t)learner * a.act_lstride + (size_t)r * a.ld_act + c);
+        return m;
+    };
+    f32x4 ebias[4];
+    u32x2 emask[4];
+    if (EARLY && wk == 0) {
 #pragma unroll
-        for (int j = 0; j < MC; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int c = c0 + (wc * MC + j) * 32 + q * 8 + (lane >> 5) * 4;
-                ebias[j][q].x = c + 0 < a.nC ? bias[c + 0] : 0.f;
-                ebias[j][q].y = c + 1 < a.nC ? bias[c + 1] : 0.f;
-                ebias[j][q].z = c + 2 < a.nC ? bias[c + 2] : 0.f;
-                ebias[j][q].w = c + 3 < a.nC ? bias[c + 3] : 0.f;
-            }
-    }
-    if (MODE == MODE_BWD && wk == 0) {
-#pragma unroll
-        for (int i = 0; i < MR; ++i) {
-            const int r = r0 + (wr * MR + i) * 32 + (lane & 31);
-#pragma unroll
-            for (int j = 0; j < MC; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int c = c0 + (wc * MC + j) * 32 + q * 8 + (lane >> 5) * 4;
-                    emask[i][j][q] = (u32x2){0u, 0u};
-                    if (r < a.nR && c < a.nC)
-                        emask[i][j][q] = *(const u32x2*)(a.act_prev + (size_t)learner * a.act_lstride + (size_t)r * a.ld_act + c);
-                }
+        for (int q = 0; q < 4; ++q) {
+            if (MODE == MODE_FWD) ebias[q] = bias_of(0, q);
+            if (MODE == MODE_BWD) emask[q] = mask_of(0, 0, q);
         }
     }
 
@@ -517,7 +516,8 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                     float v2 = acc[i][j][4 * q + 2], v3 = acc[i][j][4 * q + 3];
                     if (MODE == MODE_FWD) {
                         if (c >= a.ld_out) continue;
-                        v0 += ebias[j][q].x; v1 += ebias[j][q].y; v2 += ebias[j][q].z; v3 += ebias[j][q].w;
+                        const f32x4 bq = EARLY ? ebias[q] : bias_of(j, q);
+                        v0 += bq.x; v1 += bq.y; v2 += bq.z; v3 += bq.w;
                         if (a.relu) {
                             u32x2 o = {pack2(fmaxf(v0, 0.f), fmaxf(v1, 0.f)), pack2(fmaxf(v2, 0.f), fmaxf(v3, 0.f))};
                             *(u32x2*)((uint16_t*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
@@ -527,7 +527,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                         }
                     } else {
                         if (c >= a.nC) continue;
-                        const u32x2 m = emask[i][j][q];
+                        const u32x2 m = EARLY ? emask[q] : mask_of(i, j, q);
                         // stored activations are relu outputs (never negative): positive <=> non-zero magnitude
                         v0 = (m.x & 0x7FFFu) ? v0 : 0.f;
                         v1 = (m.x & 0x7FFF0000u) ? v1 : 0.f;
@@ -575,9 +575,11 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                     w.x -= a.lr * step.x; w.y -= a.lr * step.y; w.z -= a.lr * step.z; w.w -= a.lr * step.w;
                     __builtin_nontemporal_store(w, (f32x4*)(wbase + (size_t)r * a.nC + c));
                     u32x2 o = {pack2(w.x, w.y), pack2(w.z, w.w)};
-                    // the shadow is what the next forward pass reads: an ordinary store leaves it in the
-                    // memory-side cache (the master and the velocity, streamed once per step, bypass it)
-                    *(u32x2*)(sbase + (size_t)r * a.nC + c) = o;
+                    // The shadow is what the next forward pass reads.  When all shadows fit there, an ordinary
+                    // store leaves it in the memory-side cache (the master and the velocity, streamed once
+                    // per step, always bypass it); when they do not, it would only displace other lines.
+                    if (SHADOW_CACHED) *(u32x2*)(sbase + (size_t)r * a.nC + c) = o;
+                    else __builtin_nontemporal_store(o, (u32x2*)(sbase + (size_t)r * a.nC + c));
                 }
             }
         }
@@ -590,7 +592,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
     }
 }
 
-template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RT, bool CT, int PIPE>
+template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RT, bool CT, int PIPE, bool SC = false>
 hipError_t launch(Args a, int P, hipStream_t st) {
     a.tiles_c = (a.nC + TC - 1) / TC;
     a.tiles_r = (a.nR + TR - 1) / TR;
@@ -601,11 +603,11 @@ hipError_t launch(Args a, int P, hipStream_t st) {
     static_assert(SMEM <= 160 * 1024, "more LDS than a compute unit has");
     if (SMEM > 64 * 1024) {                     // beyond the default limit: raise it once for this kernel
         static hipError_t raised = hipFuncSetAttribute(
-            (const void*)gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE>,
+            (const void*)gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE, SC>,
             hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
         if (raised != hipSuccess) return raised;
     }
-    hipLaunchKernelGGL((gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE>), grid, dim3(64 * WR * WC * WK),
+    hipLaunchKernelGGL((gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE, SC>), grid, dim3(64 * WR * WC * WK),
                        SMEM, st, a);
     return hipGetLastError();
 }
@@ -674,7 +676,8 @@ hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     a.w = c.w; a.w_lstride = c.w_stride; a.ws = c.ws; a.ws_lstride = c.ws_stride; a.b = c.b;
     a.lr = c.lr; a.u = c.u; a.ub = c.ub; a.beta = c.beta;
     a.next_gather = c.gather ? c.next_gather : nullptr;
-    return launch<MODE_UPD, 128, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN>(a, c.P, st);
+    if (c.shadow_cached) return launch<MODE_UPD, 128, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, true>(a, c.P, st);
+    return launch<MODE_UPD, 128, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false>(a, c.P, st);
 }
 
 }  // namespace kavg

@@ -197,6 +197,14 @@ struct Bracket {
     ~Bracket() { if (on) (void)hipEventRecord(stop, c->stream); }
 };
 
+// The bf16 shadows of all learners are re-read by every forward pass.  If together they fit well
+// inside the memory-side cache of the chip (256 MB), the kernels that write them use ordinary
+// stores and the next reader finds them there; larger sets are written with streaming stores,
+// which measured faster than letting them churn the cache.
+int shadows_stay_cached(int P, size_t elems_per_learner) {
+    return (size_t)P * elems_per_learner * 2 <= ((size_t)192 << 20) ? 1 : 0;
+}
+
 LayerCall layer_call(const kavg_ctx* c, int l /*1..L*/, int k) {
     const Layout& lo = c->lo;
     const size_t esz = c->dtype == KAVG_BF16 ? 2 : 4;
@@ -207,6 +215,7 @@ LayerCall layer_call(const kavg_ctx* c, int l /*1..L*/, int k) {
     q.w = c->reps() + lo.w_off[l - 1]; q.w_stride = lo.stride;
     q.b = c->reps() + lo.b_off[l - 1];
     q.ws = c->shadow() ? c->shadow() + lo.w_off[l - 1] : nullptr; q.ws_stride = lo.stride;
+    q.shadow_cached = shadows_stay_cached(c->P, lo.stride);
     if (l == 1) {
         q.in = c->X; q.ld_in = c->dims[0]; q.in_stride = 0;
         q.gather = c->idx() + (size_t)k * c->B; q.gather_stride = (long)c->K * c->B;
@@ -438,7 +447,7 @@ int kavg_meta_update(kavg_ctx* c) {
     {
         Bracket br(c, KAVG_CLASS_META);
         KAVG_HIP(c, launch_meta_update(c->w_tilde(), c->v(), c->reps(), c->lo.stride, c->shadow(), c->lo.stride,
-                                       c->P, c->lo.n, c->mu, c->stream));
+                                       c->P, c->lo.n, c->mu, shadows_stay_cached(c->P, c->lo.stride), c->stream));
     }
     c->round += 1;
     return KAVG_OK;
@@ -582,7 +591,7 @@ int kavg_meta_update_flat(float* w_tilde_dev, float* v_dev, float* replicas_dev,
     if (P < 1 || n < 1 || replica_stride < n || !(mu >= 0.f && mu < 1.f)) return KAVG_EINVAL;
     if (shadow_dev && shadow_stride < n) return KAVG_EINVAL;
     hipError_t e = launch_meta_update(w_tilde_dev, v_dev, replicas_dev, replica_stride, shadow_dev,
-                                      shadow_stride, P, n, mu, (hipStream_t)hip_stream);
+                                      shadow_stride, P, n, mu, shadows_stay_cached(P, n), (hipStream_t)hip_stream);
     return e == hipSuccess ? KAVG_OK : KAVG_EDEVICE;
 }
 

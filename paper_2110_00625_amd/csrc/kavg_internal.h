@@ -19,9 +19,10 @@ hipError_t launch_index_import(int32_t* idx, const int32_t* user, size_t count, 
 hipError_t launch_label_check(const int32_t* y, size_t N, int C, int* flag, hipStream_t st);
 
 // ---- meta level (Algorithm 1: a, d, v, w~, restart of the learners) ----
+// shadow_cached: write the shadows with ordinary stores (they fit in the memory-side cache) or streaming ones
 hipError_t launch_meta_update(float* w_tilde, float* v, float* reps, size_t stride,
                               uint16_t* shadow, size_t sstride, int P, size_t n, float mu,
-                              hipStream_t st);
+                              int shadow_cached, hipStream_t st);
 // w^j <- w~ for all j (and shadows): the "set w^j = w~_n" of the first round
 hipError_t launch_broadcast(const float* w_tilde, float* reps, size_t stride,
                             uint16_t* shadow, size_t sstride, int P, size_t n, hipStream_t st);
@@ -43,6 +44,7 @@ struct LayerCall {
     float* w;       size_t w_stride;      // master weights of this layer (first learner)
     float* b;                               // master bias of this layer (same stride)
     uint16_t* ws;   size_t ws_stride;     // bf16 shadow of w (bf16 mode), else null
+    int shadow_cached;                    // updates store the shadow with ordinary (1) or streaming (0) stores
     // activations entering the layer: [P][B][ld_in]; or, with gather != null, rows X[gather[j][m]]
     const void* in; int ld_in; size_t in_stride;
     const int32_t* gather; long gather_stride;

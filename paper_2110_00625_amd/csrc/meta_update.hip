@@ -40,7 +40,7 @@ __device__ __forceinline__ void meta_scalar_element(float* w_tilde, float* v, fl
     }
 }
 
-template <bool SHADOW, int UNROLL>
+template <bool SHADOW, int UNROLL, bool SHADOW_CACHED>
 __global__ void __launch_bounds__(256)
 meta_update_vec_kernel(float* __restrict__ w_tilde, float* __restrict__ v, float* __restrict__ reps,
                        size_t stride, uint16_t* __restrict__ shadow, size_t sstride, int P,
@@ -71,9 +71,11 @@ meta_update_vec_kernel(float* __restrict__ w_tilde, float* __restrict__ v, float
             u16x4 h = {to_bf16_bits(wn.x), to_bf16_bits(wn.y), to_bf16_bits(wn.z), to_bf16_bits(wn.w)};
             u16x4* so = (u16x4*)shadow + i;
             const size_t ss4 = sstride / 4;
-            // ordinary stores: the shadows are what the next forward pass reads, so they may stay in
-            // the memory-side cache (the replicas above, read again only by the updates, bypass it)
-            for (int jj = 0; jj < P; ++jj) so[(size_t)jj * ss4] = h;
+            // The shadows are what the next forward pass reads: when they all fit in the memory-side
+            // cache they are written with ordinary stores and stay there (the replicas above, read
+            // again only by the updates, always bypass it).
+            if (SHADOW_CACHED) { for (int jj = 0; jj < P; ++jj) so[(size_t)jj * ss4] = h; }
+            else { for (int jj = 0; jj < P; ++jj) __builtin_nontemporal_store(h, so + (size_t)jj * ss4); }
         }
     } else {
         const size_t e = 4 * n4 + (i - n4);               // ragged tail: at most 3 parameters
@@ -92,7 +94,7 @@ static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 hipError_t launch_meta_update(float* w_tilde, float* v, float* reps, size_t stride,
                               uint16_t* shadow, size_t sstride, int P, size_t n, float mu,
-                              hipStream_t st) {
+                              int shadow_cached, hipStream_t st) {
     const float invP = 1.0f / (float)P;
     bool vec = aligned16(w_tilde) && aligned16(v) && aligned16(reps) && (stride % 4 == 0);
     if (shadow) vec = vec && (((uintptr_t)shadow & 7) == 0) && (sstride % 4 == 0);
@@ -100,11 +102,14 @@ hipError_t launch_meta_update(float* w_tilde, float* v, float* reps, size_t stri
         const size_t n4 = n / 4;
         const size_t threads = n4 + (n - 4 * n4);
         const unsigned grid = (unsigned)((threads + 255) / 256);
-        if (shadow)
-            hipLaunchKernelGGL((meta_update_vec_kernel<true, 16>), dim3(grid), dim3(256), 0, st, w_tilde, v,
+        if (shadow && shadow_cached)
+            hipLaunchKernelGGL((meta_update_vec_kernel<true, 16, true>), dim3(grid), dim3(256), 0, st, w_tilde, v,
+                               reps, stride, shadow, sstride, P, n4, n, mu, invP);
+        else if (shadow)
+            hipLaunchKernelGGL((meta_update_vec_kernel<true, 16, false>), dim3(grid), dim3(256), 0, st, w_tilde, v,
                                reps, stride, shadow, sstride, P, n4, n, mu, invP);
         else
-            hipLaunchKernelGGL((meta_update_vec_kernel<false, 16>), dim3(grid), dim3(256), 0, st, w_tilde, v,
+            hipLaunchKernelGGL((meta_update_vec_kernel<false, 16, false>), dim3(grid), dim3(256), 0, st, w_tilde, v,
                                reps, stride, shadow, sstride, P, n4, n, mu, invP);
     } else {
         const unsigned grid = (unsigned)((n + 255) / 256);
