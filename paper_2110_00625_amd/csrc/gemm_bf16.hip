@@ -422,54 +422,54 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
         }
         __syncthreads();                                // tiles are dead: the k-group reduction reuses their LDS
     } else {
-    fetch(0);
-    // Update of the first layer: the rows that the next local step samples are scattered over the data
-    // set, and its forward pass, with one slice of look-ahead, would pay the latency of such a read
-    // in every slice.  This launch is bound by its parameter stream and lasts long, so its
-    // workgroups touch those rows, one 128-byte line per lane (the learner's rows are spread over
-    // the learner's workgroups, which run on the XCD that will run its forward tiles).  The
-    // value is only kept alive until the end of the kernel.
-    if (MODE == MODE_UPD && a.next_gather) {
-        const int lines_per_row = (a.C.n_cont * 2 + 127) / 128;
-        const int lines = a.C.n_rows * lines_per_row;                 // of this learner
-        const int wgs = a.tiles_r * a.tiles_c;
-        const int per_wg = (lines + wgs - 1) / wgs;
-        const int32_t* ng = a.next_gather + (long)learner * a.C.gstride;
-        for (int t = tid; t < per_wg; t += NT) {
-            const int line = tile * per_wg + t;
-            if (line < lines) {
-                const int row = line / lines_per_row, ln = line - row * lines_per_row;
-                touched ^= *(const uint32_t*)(a.C.base + (long)ng[row] * a.C.ld + ln * 64);
+        fetch(0);
+        // Update of the first layer: the rows that the next local step samples are scattered over the data
+        // set, and its forward pass, with one slice of look-ahead, would pay the latency of such a read
+        // in every slice.  This launch is bound by its parameter stream and lasts long, so its
+        // workgroups touch those rows, one 128-byte line per lane (the learner's rows are spread over
+        // the learner's workgroups, which run on the XCD that will run its forward tiles).  The
+        // value is only kept alive until the end of the kernel.
+        if (MODE == MODE_UPD && a.next_gather) {
+            const int lines_per_row = (a.C.n_cont * 2 + 127) / 128;
+            const int lines = a.C.n_rows * lines_per_row;                 // of this learner
+            const int wgs = a.tiles_r * a.tiles_c;
+            const int per_wg = (lines + wgs - 1) / wgs;
+            const int32_t* ng = a.next_gather + (long)learner * a.C.gstride;
+            for (int t = tid; t < per_wg; t += NT) {
+                const int line = tile * per_wg + t;
+                if (line < lines) {
+                    const int row = line / lines_per_row, ln = line - row * lines_per_row;
+                    touched ^= *(const uint32_t*)(a.C.base + (long)ng[row] * a.C.ld + ln * 64);
+                }
             }
         }
-    }
-    if (PIPE == PIPE_PLAIN) {
-        for (int k0 = 0; k0 < a.nK; k0 += BK) {
+        if (PIPE == PIPE_PLAIN) {
+            for (int k0 = 0; k0 < a.nK; k0 += BK) {
+                stash(0);
+                __syncthreads();
+                if (k0 + BK < a.nK) fetch(k0 + BK);     // next slice in flight during the MFMAs
+                multiply(0);
+                if (MODE == MODE_UPD && tile_c == 0 && tid < TR) {
+                    // R tile of the update is dZ as [sample][unit]: column tid summed over the slice's samples
+#pragma unroll 8
+                    for (int k = 0; k < BK; ++k) bias_sum += bf16_to_f32(Rs[k * tpitch(TR) + tid]);
+                }
+                __syncthreads();
+            }
+        } else {
             stash(0);
             __syncthreads();
-            if (k0 + BK < a.nK) fetch(k0 + BK);     // next slice in flight during the MFMAs
-            multiply(0);
-            if (MODE == MODE_UPD && tile_c == 0 && tid < TR) {
-                // R tile of the update is dZ as [sample][unit]: column tid summed over the slice's samples
-#pragma unroll 8
-                for (int k = 0; k < BK; ++k) bias_sum += bf16_to_f32(Rs[k * tpitch(TR) + tid]);
+            if (BK < a.nK) fetch(BK);
+            int buf = 0;
+            for (int k0 = 0; k0 < a.nK; k0 += BK, buf ^= 1) {
+                if (k0 + BK < a.nK) {
+                    stash(buf ^ 1);                     // slice k0+BK, written while slice k0 is read
+                    if (k0 + 2 * BK < a.nK) fetch(k0 + 2 * BK);
+                }
+                multiply(buf);
+                __syncthreads();
             }
-            __syncthreads();
         }
-    } else {
-        stash(0);
-        __syncthreads();
-        if (BK < a.nK) fetch(BK);
-        int buf = 0;
-        for (int k0 = 0; k0 < a.nK; k0 += BK, buf ^= 1) {
-            if (k0 + BK < a.nK) {
-                stash(buf ^ 1);                     // slice k0+BK, written while slice k0 is read
-                if (k0 + 2 * BK < a.nK) fetch(k0 + 2 * BK);
-            }
-            multiply(buf);
-            __syncthreads();
-        }
-    }
     }
 
     if (WK > 1) {
