@@ -53,20 +53,21 @@ def class_model(w, learner_momentum=False):
         ld_out = ldz if l == L else d[l]
         if head and l == L:     # both head kernels: A_{L-1} twice, W_L, dZ_L, dZ_{L-1}, master/shadow of W_L
             by["head"] = P * (2 * e * B * d[l - 1] + e * wsz + 3 * e * B * ld_out + e * B * d[l - 1]
-                              + (8 + vel + (2 if bf else 0)) * wsz + (8 + vel) * d[l])
+                              + (8 + vel) * wsz + (8 + vel) * d[l])
             fl["head"] = P * 6 * B * wsz
             continue
         # forward: weights once, bias, input rows, output rows
         by["forward"] += P * (e * wsz + 4 * d[l] + e * B * d[l - 1] + (4 * B * ld_out if l == L else e * B * d[l]))
         fl["forward"] += P * 2 * B * wsz
-        # update: master read + write (+ shadow write), bias read + write, dZ and A once
-        by["update"] += P * ((8 + vel + (2 if bf else 0)) * wsz + (8 + vel) * d[l] + e * B * (ld_out + d[l - 1]))
+        # update: master read + write (fp32, or its two 16-bit planes: 4 bytes either way), bias read +
+        # write, dZ and A once
+        by["update"] += P * ((8 + vel) * wsz + (8 + vel) * d[l] + e * B * (ld_out + d[l - 1]))
         fl["update"] += P * 2 * B * wsz
         if l > 1:   # data gradient: weights once, dZ_l, mask read, dZ_{l-1} written
             by["backward"] += P * (e * wsz + e * B * ld_out + 2 * e * B * d[l - 1])
             fl["backward"] += P * 2 * B * wsz
     n = num_params(d)
-    by["meta"] = (2 * P + 4) * 4 * n + (2 * P * n if bf else 0)
+    by["meta"] = (2 * P + 4) * 4 * n
     fl["meta"] = (2 * P + 3) * n
     return by, fl
 

@@ -34,12 +34,16 @@
  *
  * dtype
  *  KAVG_FP32: every tensor and every product in fp32.
- *  KAVG_BF16: operands of every matrix product are bf16 (round to nearest
- *    even): the data set (given as bf16), a bf16 shadow of each replica's
- *    weights (refreshed by every update and by the meta step), the stored
- *    hidden activations and the back-propagated dZ_l.  Accumulation is fp32;
- *    logits, softmax, loss, biases, master parameters, the SGD update and the
- *    whole meta step are fp32.  Requires d_0..d_{L-1} to be multiples of 8.
+ *  KAVG_BF16: operands of every matrix product are bf16: the data set (given
+ *    as bf16), each replica's weights rounded to bf16 (nearest, ties away from
+ *    zero), the stored hidden activations and the back-propagated dZ_l (nearest,
+ *    ties to even).  Accumulation is fp32; logits, softmax, loss, biases, the
+ *    learners' master parameters, the SGD update and the whole meta step are
+ *    fp32.  A learner's fp32 parameters are stored as two 16-bit planes: the
+ *    bf16 value the products read, and the low 16 bits of the fp32 pattern;
+ *    together they are the exact fp32 value (kavg_replica joins them), so the
+ *    products' operand is half of the master rather than a copy beside it.
+ *    Requires d_0..d_{L-1} to be multiples of 8.
  */
 #ifndef KAVG_H
 #define KAVG_H
@@ -67,7 +71,7 @@ typedef struct kavg_ctx kavg_ctx;
 size_t kavg_num_params(int n_layers, const int* dims);
 
 /* Bytes of device workspace kavg_init needs for this configuration (global
- * model, momentum buffer, P replicas, bf16 shadows, index stream, activations,
+ * model, momentum buffer, P replicas (4 bytes per parameter in either mode), index stream, activations,
  * back-propagated gradients, losses).  Returns 0 on bad arguments. */
 size_t kavg_workspace_bytes(int P, int K, int B, int n_layers, const int* dims, int dtype);
 
@@ -88,7 +92,7 @@ int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu,
 
 /* "initialize w~_1; v <- 0" of Algorithm 1, and "set w^j = w~_1": copies n
  * floats from w0_host into the global model, zeroes the momentum buffer,
- * writes every replica (and bf16 shadow), resets round and step counters. */
+ * writes every replica, resets round and step counters. */
 int kavg_set_params(kavg_ctx* ctx, const float* w0_host);
 
 /* Resume: global model w and momentum v (host, n floats each), round counter;
@@ -120,7 +124,7 @@ int kavg_local_steps(kavg_ctx* ctx);
 
 /* The meta level of Algorithm 1 in one fused pass: average the replicas, block
  * displacement d, block momentum v <- mu v + d, w~ <- w~ + v, and rebroadcast
- * w~ to every replica (and shadow).  Asynchronous.  Increments the round. */
+ * w~ to every replica.  Asynchronous.  Increments the round. */
 int kavg_meta_update(kavg_ctx* ctx);
 
 /* Copy-outs (host pointers; each waits for the stream).  n must equal
@@ -190,7 +194,8 @@ int         kavg_destroy(kavg_ctx* ctx);            /* waits for the stream, fre
  *   w_tilde_dev [n], v_dev [n]: updated in place;
  *   replicas_dev: P replicas, replica j at replicas_dev + j*replica_stride
  *     (replica_stride >= n, in floats); read, then overwritten with w~_{n+1};
- *   shadow_dev: NULL, or bf16 copies written at shadow_dev + j*shadow_stride.
+ *   shadow_dev: NULL, or bf16 copies (nearest, ties away from zero) written at
+ *     shadow_dev + j*shadow_stride.
  * Pointers 16-byte aligned and strides multiples of 4 (8 for the shadow) take
  * the vector path; anything else takes a slower scalar path.  Asynchronous on
  * hip_stream.  Errors: KAVG_EINVAL (P < 1, n < 1, stride < n, mu outside

@@ -36,7 +36,9 @@ Readings where the paper is silent (each repeated in the design notes):
   own u across meta rounds (it is not reset when the learner restarts from
   w~), u = 0 initially.  beta = 0 is Algorithm 1 as printed.
 * mixed precision ("bf16" mode): the operands of every matrix product are
-  rounded to bf16 (nearest, ties to even): the weights as used in forward and
+  rounded to bf16 (nearest; ties to even, except the weights, whose ties go
+  away from zero -- the rounding that lets an fp32 master be kept exactly as
+  its bf16 value plus a 16-bit remainder): the weights as used in forward and
   data-gradient products, the stored hidden activations, and the gradient
   dZ_l that flows backward through layer l (used for the weight gradient, the
   bias gradient and the data gradient alike).  Accumulation, logits, softmax,
@@ -99,6 +101,15 @@ def rne_bf16(x: np.ndarray) -> np.ndarray:
     the magnitudes that occur)."""
     m, e = np.frexp(np.asarray(x, dtype=np.float64))
     return np.ldexp(np.rint(m * 256.0) / 256.0, e)
+
+
+def rna_bf16(x: np.ndarray) -> np.ndarray:
+    """Nearest bf16 value of each float64, ties away from zero.  This is the
+    rounding of the *weights* in the mixed-precision reading: adding half a
+    unit to the magnitude and cutting the fp32 pattern to its top 16 bits.
+    It differs from rne_bf16 only on exact ties."""
+    m, e = np.frexp(np.asarray(x, dtype=np.float64))
+    return np.ldexp(np.sign(m) * np.floor(np.abs(m) * 256.0 + 0.5) / 256.0, e)
 
 
 def _identity(x):
@@ -170,8 +181,9 @@ def backward(Ws, Zs, As, dZL, q=_identity):
 def minibatch_gradient(w, dims, Xb, yb, bf16=False):
     """(mean loss, flat gradient) of the minibatch objective at w."""
     q = rne_bf16 if bf16 else _identity
+    qw = rna_bf16 if bf16 else _identity
     Ws, bs = unpack(w, dims)
-    Wq = [q(W) for W in Ws]
+    Wq = [qw(W) for W in Ws]
     Zs, As = forward(Wq, bs, Xb, q)
     loss, dZL = softmax_cross_entropy(Zs[-1], yb)
     gWs, gbs = backward(Wq, Zs, As, dZL, q)

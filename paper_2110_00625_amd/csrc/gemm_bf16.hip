@@ -35,6 +35,7 @@
 // memory-contiguous extent is a multiple of 8 elements (hidden widths are
 // required to be, the class count is padded in the logits / dZ_L buffers).
 #include "kavg_internal.h"
+#include "split.h"
 
 namespace kavg {
 
@@ -66,14 +67,16 @@ struct Args {
     Operand R, C;
     int nR, nC, nK;
     int tiles_r, tiles_c, total_wg, chunk;       // workgroup -> tile map (set by launch)
-    // forward
-    const float* bias; size_t bias_lstride;
+    // forward: bias as hi / lo planes (split.h)
+    const uint16_t* bias_hi; const uint16_t* bias_lo; size_t bias_lstride;
     void* out; size_t out_lstride; int ld_out;   // bf16 activations or fp32 logits
     int relu;                                    // 1: hidden layer (bf16 out), 0: last layer (fp32 out)
     // backward-data
     const uint16_t* act_prev; size_t act_lstride; int ld_act;
-    // update
-    float* w; size_t w_lstride; uint16_t* ws; size_t ws_lstride; float* b;
+    // update: the fp32 master as two 16-bit planes (split.h): ws = hi (the bf16 operands of the other
+    // products), wlo = lo; bias planes likewise; all with ws_lstride between learners
+    uint16_t* ws; uint16_t* wlo; size_t ws_lstride; uint16_t* bhi; uint16_t* blo;
+    size_t w_lstride;                            // between learners in the velocity arrays
     float lr;
     float* u; float* ub; float beta;             // velocities of weights / bias (stride w_lstride), null: plain SGD
     const int32_t* next_gather;                  // rows of C's data set that the next step gathers (stride C.gstride), or null
@@ -349,20 +352,30 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
 
     // Update: the fp32 master tile is independent of the product, so its loads go out first and
     // are in flight during the whole contraction (the kernel is bound by this stream, not by MFMAs).
-    constexpr int F4_PER_ROW = WTC / 4;
-    constexpr int ROWS_PER_IT = 64 / F4_PER_ROW;
+    // In the epilogue a lane owns eight consecutive columns of a row: 16 bytes of either plane.
+    constexpr int L8_PER_ROW = WTC / 8;
+    constexpr int ROWS_PER_IT = 64 / L8_PER_ROW;
     constexpr int ITS = 32 / ROWS_PER_IT;
-    f32x4 mst[MODE == MODE_UPD ? MR : 1][MODE == MODE_UPD ? ITS : 1];
+    u32x4 mhi[MODE == MODE_UPD ? MR : 1][MODE == MODE_UPD ? ITS : 1];
+    u32x4 mlo[MODE == MODE_UPD ? MR : 1][MODE == MODE_UPD ? ITS : 1];
     if (MODE == MODE_UPD) {
-        const float* wbase = a.w + (size_t)learner * a.w_lstride;
-        const int c = c0 + wc * WTC + (lane % F4_PER_ROW) * 4;
+        const uint16_t* hbase = a.ws + (size_t)learner * a.ws_lstride;
+        const uint16_t* lbase = a.wlo + (size_t)learner * a.ws_lstride;
+        const int c = c0 + wc * WTC + (lane % L8_PER_ROW) * 8;
 #pragma unroll
         for (int i = 0; i < MR; ++i)
 #pragma unroll
             for (int it = 0; it < ITS; ++it) {
-                const int r = r0 + (wr * MR + i) * 32 + it * ROWS_PER_IT + lane / F4_PER_ROW;
-                mst[i][it] = (f32x4){0.f, 0.f, 0.f, 0.f};
-                if (r < a.nR && c < a.nC) mst[i][it] = __builtin_nontemporal_load((const f32x4*)(wbase + (size_t)r * a.nC + c));
+                const int r = r0 + (wr * MR + i) * 32 + it * ROWS_PER_IT + lane / L8_PER_ROW;
+                mhi[i][it] = (u32x4){0u, 0u, 0u, 0u};
+                mlo[i][it] = (u32x4){0u, 0u, 0u, 0u};
+                if (r < a.nR && c < a.nC) {
+                    // hi was left in the memory-side cache by the previous writer when it fits there
+                    // (otherwise it is streamed like lo, so as not to push anything else out)
+                    mhi[i][it] = SHADOW_CACHED ? *(const u32x4*)(hbase + (size_t)r * a.nC + c)
+                                               : __builtin_nontemporal_load((const u32x4*)(hbase + (size_t)r * a.nC + c));
+                    mlo[i][it] = __builtin_nontemporal_load((const u32x4*)(lbase + (size_t)r * a.nC + c));
+                }
             }
     }
 
@@ -372,13 +385,12 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
     // Only the wavefronts of k group 0 reach the epilogue.
     constexpr bool EARLY = MR * MC == 1;
     auto bias_of = [&](int j, int q) {
-        const float* bias = a.bias + (size_t)learner * a.bias_lstride;
+        const uint16_t* bh = a.bias_hi + (size_t)learner * a.bias_lstride;
+        const uint16_t* bl = a.bias_lo + (size_t)learner * a.bias_lstride;
         const int c = c0 + (wc * MC + j) * 32 + q * 8 + (lane >> 5) * 4;
+        auto one = [&](int cc) { return cc < a.nC ? __builtin_bit_cast(float, split_join(bh[cc], bl[cc])) : 0.f; };
         f32x4 b;
-        b.x = c + 0 < a.nC ? bias[c + 0] : 0.f;
-        b.y = c + 1 < a.nC ? bias[c + 1] : 0.f;
-        b.z = c + 2 < a.nC ? bias[c + 2] : 0.f;
-        b.w = c + 3 < a.nC ? bias[c + 3] : 0.f;
+        b.x = one(c + 0); b.y = one(c + 1); b.z = one(c + 2); b.w = one(c + 3);
         return b;
     };
     auto mask_of = [&](int i, int j, int q) {
@@ -544,9 +556,9 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
         // 32-row block of its accumulators through a private LDS patch so that a lane ends up with four
         // consecutive columns of a row and 64/(WTC/4) rows are covered per access, WTC*4 contiguous bytes each.
         float* stage = (float*)smem + wave * 32 * SPITCH;
-        float* wbase = a.w + (size_t)learner * a.w_lstride;
-        uint16_t* sbase = a.ws + (size_t)learner * a.ws_lstride;
-        const int rr = lane / F4_PER_ROW, cc = (lane % F4_PER_ROW) * 4;
+        uint16_t* hbase = a.ws + (size_t)learner * a.ws_lstride;
+        uint16_t* lbase = a.wlo + (size_t)learner * a.ws_lstride;
+        const int rr = lane / L8_PER_ROW, cc = (lane % L8_PER_ROW) * 8;
         const int c = c0 + wc * WTC + cc;
 #pragma unroll
         for (int i = 0; i < MR; ++i) {
@@ -563,30 +575,46 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
 #pragma unroll
             for (int it = 0; it < ITS; ++it) {
                 const int r = rblk + it * ROWS_PER_IT + rr;
-                const f32x4 g = *(const f32x4*)(stage + (it * ROWS_PER_IT + rr) * SPITCH + cc);
+                const float* gp = stage + (it * ROWS_PER_IT + rr) * SPITCH + cc;
+                const f32x4 g0 = *(const f32x4*)gp, g1 = *(const f32x4*)(gp + 4);
                 if (r < a.nR && c < a.nC) {
-                    f32x4 w = mst[i][it];
-                    f32x4 step = g;
+                    float step[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
                     if (a.u) {                                  // heavy ball inside the learner
                         f32x4* up = (f32x4*)(a.u + (size_t)learner * a.w_lstride + (size_t)r * a.nC + c);
-                        step = a.beta * __builtin_nontemporal_load(up) + g;
-                        __builtin_nontemporal_store(step, up);
+                        const f32x4 u0 = __builtin_nontemporal_load(up), u1 = __builtin_nontemporal_load(up + 1);
+                        const float uo[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) step[e] = a.beta * uo[e] + step[e];
+                        __builtin_nontemporal_store((f32x4){step[0], step[1], step[2], step[3]}, up);
+                        __builtin_nontemporal_store((f32x4){step[4], step[5], step[6], step[7]}, up + 1);
                     }
-                    w.x -= a.lr * step.x; w.y -= a.lr * step.y; w.z -= a.lr * step.z; w.w -= a.lr * step.w;
-                    __builtin_nontemporal_store(w, (f32x4*)(wbase + (size_t)r * a.nC + c));
-                    u32x2 o = {pack2(w.x, w.y), pack2(w.z, w.w)};
-                    // The shadow is what the next forward pass reads.  When all shadows fit there, an ordinary
-                    // store leaves it in the memory-side cache (the master and the velocity, streamed once
-                    // per step, always bypass it); when they do not, it would only displace other lines.
-                    if (SHADOW_CACHED) *(u32x2*)(sbase + (size_t)r * a.nC + c) = o;
-                    else __builtin_nontemporal_store(o, (u32x2*)(sbase + (size_t)r * a.nC + c));
+                    u32x4 oh, ol;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        uint32_t b0, b1, h2, l2;
+                        split_join2(mhi[i][it][q], mlo[i][it][q], b0, b1);
+                        const float w0 = __builtin_bit_cast(float, b0) - a.lr * step[2 * q];
+                        const float w1 = __builtin_bit_cast(float, b1) - a.lr * step[2 * q + 1];
+                        split_pack2(__builtin_bit_cast(uint32_t, w0), __builtin_bit_cast(uint32_t, w1), h2, l2);
+                        oh[q] = h2; ol[q] = l2;
+                    }
+                    // The hi plane is what the next forward pass reads.  When the hi planes of all learners
+                    // fit there, an ordinary store leaves it in the memory-side cache; when they do not, it
+                    // would only displace other lines.  The lo plane (and the velocity) is streamed once
+                    // per step and always bypasses the cache.
+                    if (SHADOW_CACHED) *(u32x4*)(hbase + (size_t)r * a.nC + c) = oh;
+                    else __builtin_nontemporal_store(oh, (u32x4*)(hbase + (size_t)r * a.nC + c));
+                    __builtin_nontemporal_store(ol, (u32x4*)(lbase + (size_t)r * a.nC + c));
                 }
             }
         }
         if (tile_c == 0 && tid < TR && r0 + tid < a.nR) {
             const size_t at = (size_t)learner * a.w_lstride + r0 + tid;
             if (a.ub) { bias_sum = a.beta * a.ub[at] + bias_sum; a.ub[at] = bias_sum; }
-            a.b[at] = a.b[at] - a.lr * bias_sum;
+            const size_t sat = (size_t)learner * a.ws_lstride + r0 + tid;
+            const float b = __builtin_bit_cast(float, split_join(a.bhi[sat], a.blo[sat])) - a.lr * bias_sum;
+            a.bhi[sat] = (uint16_t)split_hi(__builtin_bit_cast(uint32_t, b));
+            a.blo[sat] = (uint16_t)split_lo(__builtin_bit_cast(uint32_t, b));
         }
         asm volatile("" :: "v"(touched));               // the touched lines' loads are not dead code
     }
@@ -653,7 +681,7 @@ hipError_t bf16_forward(const LayerCall& c, hipStream_t st) {
     a.R = {(const uint16_t*)c.in, c.gather ? 0 : c.in_stride, c.ld_in, c.gather, c.gather_stride, c.B, c.d_in};
     a.C = {c.ws, c.ws_stride, c.d_in, nullptr, 0, c.d_out, c.d_in};
     a.nR = c.B; a.nC = c.d_out; a.nK = c.d_in;
-    a.bias = c.b; a.bias_lstride = c.w_stride;
+    a.bias_hi = c.bhi; a.bias_lo = c.blo; a.bias_lstride = c.ws_stride;
     a.out = c.out; a.out_lstride = c.out_stride; a.ld_out = c.ld_out; a.relu = c.relu;
     return launch_tiled<MODE_FWD, false, false>(a, c.P, pick_tile(MODE_FWD, a.nR, a.nC, c.P), st);
 }
@@ -673,12 +701,12 @@ hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     a.R = {(const uint16_t*)c.dz, c.dz_stride, c.ld_dz, nullptr, 0, c.B, c.ld_dz};         // memory row = k: R(r, k) = dZ[k][r]
     a.C = {(const uint16_t*)c.in, c.gather ? 0 : c.in_stride, c.ld_in, c.gather, c.gather_stride, c.B, c.d_in};
     a.nR = c.d_out; a.nC = c.d_in; a.nK = c.B;
-    a.w = c.w; a.w_lstride = c.w_stride; a.ws = c.ws; a.ws_lstride = c.ws_stride; a.b = c.b;
+    a.ws = c.ws; a.wlo = c.wlo; a.ws_lstride = c.ws_stride; a.bhi = c.bhi; a.blo = c.blo; a.w_lstride = c.w_stride;
     a.lr = c.lr; a.u = c.u; a.ub = c.ub; a.beta = c.beta;
     a.next_gather = c.gather ? c.next_gather : nullptr;
     // Tile shapes from measured sweeps (whole rounds, same box): 64x64 where the shadows stay cached
     // (CIFAR-MLP: +2 % over 128x128), 64x128 where they stream (the 4096-wide workloads: +3 %).
-    if (c.shadow_cached) return launch<MODE_UPD, 64, 64, 2, 2, 1, 64, true, true, PIPE_PLAIN, true>(a, c.P, st);
+    if (c.shadow_cached) return launch<MODE_UPD, 128, 64, 4, 1, 1, 64, true, true, PIPE_PLAIN, true>(a, c.P, st);
     return launch<MODE_UPD, 64, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false>(a, c.P, st);
 }
 

@@ -18,6 +18,7 @@
 // bf16 (round to nearest even) before any use, logits / softmax / loss / bias
 // / master update in fp32, shadow refreshed from the updated master.
 #include "kavg_internal.h"
+#include "split.h"
 
 namespace kavg {
 
@@ -63,9 +64,10 @@ struct HeadArgs {
     const void* act; int ld_act; size_t act_lstride;      // A_{L-1} [P][B][ld_act], or the data set when gather != null
     const int32_t* gather; long gather_lstride;           // row s of learner j is data row gather[j*gather_lstride + s]
     const void* wmul; size_t wmul_lstride;                // weights as multiplied: bf16 shadow or fp32 master, [C][d]
-    float* wmaster; size_t w_lstride;                     // fp32 master of the same layer
-    uint16_t* wshadow; size_t ws_lstride;                 // bf16 shadow to refresh (null in fp32)
-    float* bias;                                          // fp32 master bias (stride w_lstride)
+    float* wmaster; size_t w_lstride;                     // fp32 mode: the layer's weights
+    float* bias;                                          // fp32 mode: its bias (stride w_lstride)
+    uint16_t* whi; uint16_t* wlo; size_t ws_lstride;      // bf16 mode: hi / lo planes of the weights (split.h)
+    uint16_t* bhi; uint16_t* blo;                         // bf16 mode: hi / lo planes of the bias (stride ws_lstride)
     const int32_t* y;                                     // labels of the data set
     void* dz; int ldz; size_t dz_lstride;                 // dZ_L [P][B][ldz]
     void* dz_prev; size_t dz_prev_lstride;                // dZ_{L-1} [P][B][d], null for a single-layer model
@@ -94,10 +96,15 @@ __global__ void __launch_bounds__(256) head_forward_backward_kernel(HeadArgs a) 
     const int pieces = a.d / N;
     const int label_raw = a.y[sample];
     float bias_c[CT];
-    {
-        const float* bias = a.bias + (size_t)learner * a.w_lstride;
 #pragma unroll
-        for (int c = 0; c < CT; ++c) bias_c[c] = bias[c < a.C ? c : a.C - 1];
+    for (int c = 0; c < CT; ++c) {
+        const int cc = c < a.C ? c : a.C - 1;
+        if (BF16) {
+            const size_t at = (size_t)learner * a.ws_lstride + cc;
+            bias_c[c] = __builtin_bit_cast(float, split_join(a.bhi[at], a.blo[at]));
+        } else {
+            bias_c[c] = a.bias[(size_t)learner * a.w_lstride + cc];
+        }
     }
     size_t wrow[CT];
 #pragma unroll
@@ -266,22 +273,32 @@ __global__ void __launch_bounds__(256) head_update_kernel(HeadArgs a) {
 #pragma unroll
                 for (int e = 0; e < N; ++e) mine[e] = acc[c][e];
             }
-        const size_t wat = (size_t)learner * a.w_lstride + (size_t)grp * a.d + (size_t)q * N;
-        float* wm = a.wmaster + wat;
+        const size_t uat = (size_t)learner * a.w_lstride + (size_t)grp * a.d + (size_t)q * N;   // velocity (fp32 layout)
         if (a.u) {                                            // heavy ball inside the learner
 #pragma unroll
-            for (int e = 0; e < N; ++e) { mine[e] = a.beta * a.u[wat + e] + mine[e]; a.u[wat + e] = mine[e]; }
+            for (int e = 0; e < N; ++e) { mine[e] = a.beta * a.u[uat + e] + mine[e]; a.u[uat + e] = mine[e]; }
         }
-        float w[N];
-#pragma unroll
-        for (int e = 0; e < N; ++e) w[e] = wm[e] - a.lr * mine[e];
-#pragma unroll
-        for (int e = 0; e < N; ++e) wm[e] = w[e];
         if (BF16) {
-            u32x4 o;
+            // the master lives in two 16-bit planes; the hi plane is what the next products read
+            const size_t at = (size_t)learner * a.ws_lstride + (size_t)grp * a.d + (size_t)q * N;
+            const u32x4 h = *(const u32x4*)(a.whi + at), l = *(const u32x4*)(a.wlo + at);
+            u32x4 oh, ol;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) o[i] = (uint32_t)bf16_bits(w[(2 * i) % N]) | ((uint32_t)bf16_bits(w[(2 * i + 1) % N]) << 16);
-            *(u32x4*)(a.wshadow + (size_t)learner * a.ws_lstride + (size_t)grp * a.d + (size_t)q * N) = o;
+            for (int i = 0; i < 4; ++i) {
+                uint32_t b0, b1;
+                split_join2(h[i], l[i], b0, b1);
+                const float w0 = __builtin_bit_cast(float, b0) - a.lr * mine[(2 * i) % N];
+                const float w1 = __builtin_bit_cast(float, b1) - a.lr * mine[(2 * i + 1) % N];
+                uint32_t h2, l2;
+                split_pack2(__builtin_bit_cast(uint32_t, w0), __builtin_bit_cast(uint32_t, w1), h2, l2);
+                oh[i] = h2; ol[i] = l2;
+            }
+            *(u32x4*)(a.whi + at) = oh;
+            *(u32x4*)(a.wlo + at) = ol;
+        } else {
+            float* wm = a.wmaster + uat;
+#pragma unroll
+            for (int e = 0; e < N; ++e) wm[e] = wm[e] - a.lr * mine[e];
         }
     }
     if (blockIdx.x == 0 && wave == 0 && pl == 0 && grp < a.C) {   // every lane holds the full column sums
@@ -290,7 +307,14 @@ __global__ void __launch_bounds__(256) head_update_kernel(HeadArgs a) {
         for (int c = 0; c < CT; ++c) if (c == grp) mine = bsum[c];
         const size_t at = (size_t)learner * a.w_lstride + grp;
         if (a.ub) { mine = a.beta * a.ub[at] + mine; a.ub[at] = mine; }
-        a.bias[at] = a.bias[at] - a.lr * mine;
+        if (BF16) {
+            const size_t sat = (size_t)learner * a.ws_lstride + grp;
+            const float b = __builtin_bit_cast(float, split_join(a.bhi[sat], a.blo[sat])) - a.lr * mine;
+            a.bhi[sat] = (uint16_t)split_hi(__builtin_bit_cast(uint32_t, b));
+            a.blo[sat] = (uint16_t)split_lo(__builtin_bit_cast(uint32_t, b));
+        } else {
+            a.bias[at] = a.bias[at] - a.lr * mine;
+        }
     }
 }
 
@@ -300,8 +324,9 @@ HeadArgs make_args(const LayerCall& c, const int32_t* y, const int32_t* idx, lon
     a.gather = idx; a.gather_lstride = idx_lstride;
     a.wmul = bf16 ? (const void*)c.ws : (const void*)c.w;
     a.wmul_lstride = bf16 ? c.ws_stride : c.w_stride;
-    a.wmaster = c.w; a.w_lstride = c.w_stride; a.wshadow = bf16 ? c.ws : nullptr; a.ws_lstride = c.ws_stride;
-    a.bias = c.b; a.y = y;
+    a.wmaster = c.w; a.w_lstride = c.w_stride; a.bias = c.b;
+    a.whi = c.ws; a.wlo = c.wlo; a.ws_lstride = c.ws_stride; a.bhi = c.bhi; a.blo = c.blo;
+    a.y = y;
     a.dz = (void*)c.dz; a.ldz = c.ld_dz; a.dz_lstride = c.dz_stride;
     a.dz_prev = c.dz_prev; a.dz_prev_lstride = c.dz_prev_stride;
     a.rowloss = rowloss;

@@ -12,6 +12,7 @@
 
 #include "../../include/kavg.h"
 #include "kavg_internal.h"
+#include "split.h"
 
 using namespace kavg;
 
@@ -58,7 +59,9 @@ Layout make_layout(int P, int K, int B, int L, const int* dims, int dtype) {
     auto take = [&](size_t bytes) { size_t at = p; p = round_up(p + bytes, ALIGN); return at; };
     lo.off_w = take(lo.stride * 4);
     lo.off_v = take(lo.stride * 4);
-    lo.off_reps = take((size_t)P * lo.stride * 4);
+    // fp32 mode: P replicas of fp32.  bf16 mode: every replica as two 16-bit planes (split.h), the
+    // lo planes where the fp32 replicas would be, the hi planes (the bf16 operands) after them.
+    lo.off_reps = take((size_t)P * lo.stride * (dtype == KAVG_BF16 ? 2 : 4));
     lo.off_shadow = dtype == KAVG_BF16 ? take((size_t)P * lo.stride * 2) : 0;
     lo.off_idx = take((size_t)P * K * B * 4);
     lo.off_flag = take(ALIGN);
@@ -120,8 +123,9 @@ struct kavg_ctx {
 
     float* w_tilde() const { return (float*)(ws + lo.off_w); }
     float* v() const { return (float*)(ws + lo.off_v); }
-    float* reps() const { return (float*)(ws + lo.off_reps); }
-    uint16_t* shadow() const { return dtype == KAVG_BF16 ? (uint16_t*)(ws + lo.off_shadow) : nullptr; }
+    float* reps() const { return dtype == KAVG_BF16 ? nullptr : (float*)(ws + lo.off_reps); }            // fp32 mode
+    uint16_t* lo_planes() const { return dtype == KAVG_BF16 ? (uint16_t*)(ws + lo.off_reps) : nullptr; }    // bf16 mode
+    uint16_t* hi_planes() const { return dtype == KAVG_BF16 ? (uint16_t*)(ws + lo.off_shadow) : nullptr; }
     int32_t* idx() const { return (int32_t*)(ws + lo.off_idx); }
     int* flag() const { return (int*)(ws + lo.off_flag); }
     float* logits() const { return (float*)(ws + lo.off_logits); }
@@ -167,8 +171,12 @@ int install_global(kavg_ctx* c, const float* w_host, const float* v_host) {
         KAVG_HIP(c, hipMemcpyAsync(c->v(), v_host, c->lo.n * 4, hipMemcpyHostToDevice, c->stream));
     else
         KAVG_HIP(c, hipMemsetAsync(c->v(), 0, c->lo.stride * 4, c->stream));
-    KAVG_HIP(c, launch_broadcast(c->w_tilde(), c->reps(), c->lo.stride, c->shadow(), c->lo.stride, c->P,
-                                 c->lo.n, c->stream));
+    if (c->dtype == KAVG_BF16)
+        KAVG_HIP(c, launch_broadcast_split(c->w_tilde(), c->hi_planes(), c->lo_planes(), c->lo.stride, c->P,
+                                           c->lo.n, c->stream));
+    else
+        KAVG_HIP(c, launch_broadcast(c->w_tilde(), c->reps(), c->lo.stride, nullptr, c->lo.stride, c->P,
+                                     c->lo.n, c->stream));
     if (c->vel) KAVG_HIP(c, hipMemsetAsync(c->vel, 0, (size_t)c->P * c->lo.stride * 4, c->stream));
     KAVG_HIP(c, hipStreamSynchronize(c->stream));   // host buffers may be reused by the caller
     c->have_params = true;
@@ -212,9 +220,14 @@ LayerCall layer_call(const kavg_ctx* c, int l /*1..L*/, int k) {
     LayerCall q = {};
     q.P = c->P; q.B = c->B;
     q.d_in = c->dims[l - 1]; q.d_out = c->dims[l];
-    q.w = c->reps() + lo.w_off[l - 1]; q.w_stride = lo.stride;
-    q.b = c->reps() + lo.b_off[l - 1];
-    q.ws = c->shadow() ? c->shadow() + lo.w_off[l - 1] : nullptr; q.ws_stride = lo.stride;
+    q.w_stride = lo.stride; q.ws_stride = lo.stride;
+    if (c->dtype == KAVG_BF16) {
+        q.ws = c->hi_planes() + lo.w_off[l - 1];  q.wlo = c->lo_planes() + lo.w_off[l - 1];
+        q.bhi = c->hi_planes() + lo.b_off[l - 1]; q.blo = c->lo_planes() + lo.b_off[l - 1];
+    } else {
+        q.w = c->reps() + lo.w_off[l - 1];
+        q.b = c->reps() + lo.b_off[l - 1];
+    }
     q.shadow_cached = shadows_stay_cached(c->P, lo.stride);
     if (l == 1) {
         q.in = c->X; q.ld_in = c->dims[0]; q.in_stride = 0;
@@ -446,8 +459,13 @@ int kavg_meta_update(kavg_ctx* c) {
     if (!c->have_params) return fail(c, KAVG_ESTATE, "no parameters: call kavg_set_params first");
     {
         Bracket br(c, KAVG_CLASS_META);
-        KAVG_HIP(c, launch_meta_update(c->w_tilde(), c->v(), c->reps(), c->lo.stride, c->shadow(), c->lo.stride,
-                                       c->P, c->lo.n, c->mu, shadows_stay_cached(c->P, c->lo.stride), c->stream));
+        if (c->dtype == KAVG_BF16)
+            KAVG_HIP(c, launch_meta_update_split(c->w_tilde(), c->v(), c->hi_planes(), c->lo_planes(), c->lo.stride,
+                                                 c->P, c->lo.n, c->mu, shadows_stay_cached(c->P, c->lo.stride),
+                                                 c->stream));
+        else
+            KAVG_HIP(c, launch_meta_update(c->w_tilde(), c->v(), c->reps(), c->lo.stride, nullptr, c->lo.stride,
+                                           c->P, c->lo.n, c->mu, 0, c->stream));
     }
     c->round += 1;
     return KAVG_OK;
@@ -477,7 +495,17 @@ int kavg_replica(kavg_ctx* c, int j, float* out_host, size_t n) {
     if (!out_host || n != c->lo.n) return fail(c, KAVG_EINVAL, "need a buffer of exactly %zu floats", c->lo.n);
     if (j < 0 || j >= c->P) return fail(c, KAVG_EINVAL, "learner %d outside [0,%d)", j, c->P);
     if (!c->have_params) return fail(c, KAVG_ESTATE, "no parameters yet");
-    return copy_out(c, c->reps() + (size_t)j * c->lo.stride, out_host, n * 4);
+    if (c->dtype != KAVG_BF16) return copy_out(c, c->reps() + (size_t)j * c->lo.stride, out_host, n * 4);
+    // bf16 mode: fetch the learner's two planes and join them into fp32 values on the host
+    std::vector<uint16_t> hi(n), lo(n);
+    int rc = copy_out(c, c->hi_planes() + (size_t)j * c->lo.stride, hi.data(), n * 2);
+    if (rc == KAVG_OK) rc = copy_out(c, c->lo_planes() + (size_t)j * c->lo.stride, lo.data(), n * 2);
+    if (rc != KAVG_OK) return rc;
+    for (size_t e = 0; e < n; ++e) {
+        const uint32_t bits = split_join(hi[e], lo[e]);
+        memcpy(out_host + e, &bits, 4);
+    }
+    return KAVG_OK;
 }
 
 int kavg_losses(kavg_ctx* c, float* out_host) {

@@ -23,6 +23,11 @@ hipError_t launch_label_check(const int32_t* y, size_t N, int C, int* flag, hipS
 hipError_t launch_meta_update(float* w_tilde, float* v, float* reps, size_t stride,
                               uint16_t* shadow, size_t sstride, int P, size_t n, float mu,
                               int shadow_cached, hipStream_t st);
+// the same step on replicas stored as hi / lo planes (split.h), [P][stride] 16-bit each
+hipError_t launch_meta_update_split(float* w_tilde, float* v, uint16_t* hi, uint16_t* lo, size_t stride,
+                                    int P, size_t n, float mu, int hi_cached, hipStream_t st);
+hipError_t launch_broadcast_split(const float* w_tilde, uint16_t* hi, uint16_t* lo, size_t stride,
+                                  int P, size_t n, hipStream_t st);
 // w^j <- w~ for all j (and shadows): the "set w^j = w~_n" of the first round
 hipError_t launch_broadcast(const float* w_tilde, float* reps, size_t stride,
                             uint16_t* shadow, size_t sstride, int P, size_t n, hipStream_t st);
@@ -40,10 +45,14 @@ hipError_t launch_loss_mean(const float* rowloss, float* losses, int KP, int B, 
 struct LayerCall {
     int P, B;              // learners, rows per learner
     int d_in, d_out;       // layer shape: W [d_out][d_in]
-    // parameters: learner j's W at w + j*w_stride (fp32 master) / ws + j*ws_stride (bf16 shadow)
-    float* w;       size_t w_stride;      // master weights of this layer (first learner)
-    float* b;                               // master bias of this layer (same stride)
-    uint16_t* ws;   size_t ws_stride;     // bf16 shadow of w (bf16 mode), else null
+    // parameters, fp32 mode: learner j's W at w + j*w_stride, bias at b + j*w_stride
+    float* w;       size_t w_stride;      // weights of this layer (first learner); null in bf16 mode
+    float* b;                               // bias of this layer (same stride); null in bf16 mode
+    // parameters, bf16 mode: every fp32 master value is stored as two 16-bit planes (split.h):
+    // ws = the bf16 values the products read, wlo = the remainders; same for the bias
+    uint16_t* ws;   size_t ws_stride;     // hi plane of the weights (first learner), else null
+    uint16_t* wlo;                          // lo plane of the weights (stride ws_stride)
+    uint16_t* bhi;  uint16_t* blo;          // hi / lo planes of the bias (stride ws_stride)
     int shadow_cached;                    // updates store the shadow with ordinary (1) or streaming (0) stores
     // activations entering the layer: [P][B][ld_in]; or, with gather != null, rows X[gather[j][m]]
     const void* in; int ld_in; size_t in_stride;

@@ -12,15 +12,15 @@
 // loads are issued UNROLL at a time so that many are in flight per lane.
 // Replica loads and stores are streaming (non-temporal): nothing is reused.
 #include "kavg_internal.h"
+#include "split.h"
 
 namespace kavg {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ uint16_t to_bf16_bits(float x) {
-    __bf16 h = (__bf16)x;                 // round to nearest even
-    return __builtin_bit_cast(uint16_t, h);
+__device__ __forceinline__ uint16_t to_bf16_bits(float x) {     // weights: nearest, ties away from zero
+    return (uint16_t)split_hi(__builtin_bit_cast(uint32_t, x));
 }
 
 __device__ __forceinline__ void meta_scalar_element(float* w_tilde, float* v, float* reps, size_t stride,
@@ -116,6 +116,136 @@ hipError_t launch_meta_update(float* w_tilde, float* v, float* reps, size_t stri
         hipLaunchKernelGGL(meta_update_scalar_kernel, dim3(grid), dim3(256), 0, st, w_tilde, v, reps,
                            stride, shadow, sstride, P, n, mu, invP);
     }
+    return hipGetLastError();
+}
+
+// ---- the same step on replicas stored as hi / lo planes -------------------------------------
+// Each lane owns eight consecutive parameters: 16 bytes of either plane per learner.  Traffic per
+// parameter and pass: P*(2+2) bytes read, P*(2+2) written, plus w~ and v: (2P+4)*4 bytes -- the
+// refreshed bf16 values are part of the replicas, not an extra copy.  The hi planes are what the
+// next forward pass reads (ordinary stores when they fit the memory-side cache); the lo planes
+// are only read again by the updates and are streamed.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void meta_split_scalar_element(float* w_tilde, float* v, uint16_t* hi, uint16_t* lo,
+                                                          size_t stride, int P, size_t e, float mu, float invP) {
+    const float wt = w_tilde[e];
+    float acc = 0.f;
+    for (int j = 0; j < P; ++j) {
+        const size_t at = (size_t)j * stride + e;
+        acc += __builtin_bit_cast(float, split_join(hi[at], lo[at])) - wt;
+    }
+    const float vn = mu * v[e] + acc * invP;
+    const float wn = wt + vn;
+    v[e] = vn;
+    w_tilde[e] = wn;
+    const uint32_t b = __builtin_bit_cast(uint32_t, wn);
+    for (int j = 0; j < P; ++j) {
+        const size_t at = (size_t)j * stride + e;
+        hi[at] = (uint16_t)split_hi(b);
+        lo[at] = (uint16_t)split_lo(b);
+    }
+}
+
+template <int UNROLL, bool HI_CACHED>
+__global__ void __launch_bounds__(256)
+meta_update_split_kernel(float* __restrict__ w_tilde, float* __restrict__ v, uint16_t* __restrict__ hi,
+                         uint16_t* __restrict__ lo, size_t stride, int P, size_t n8, size_t n, float mu,
+                         float invP) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n8) {
+        float wt[8], acc[8];
+        {
+            const f32x4 a = ((const f32x4*)w_tilde)[2 * i], b = ((const f32x4*)w_tilde)[2 * i + 1];
+            wt[0] = a.x; wt[1] = a.y; wt[2] = a.z; wt[3] = a.w; wt[4] = b.x; wt[5] = b.y; wt[6] = b.z; wt[7] = b.w;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+        const u32x4* ph = (const u32x4*)hi + i;
+        const u32x4* pl = (const u32x4*)lo + i;
+        const size_t s8 = stride / 8;
+        auto add = [&](const u32x4& h, const u32x4& l) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint32_t b0, b1;
+                split_join2(h[q], l[q], b0, b1);
+                acc[2 * q] += __builtin_bit_cast(float, b0) - wt[2 * q];
+                acc[2 * q + 1] += __builtin_bit_cast(float, b1) - wt[2 * q + 1];
+            }
+        };
+        int j = 0;
+        for (; j + UNROLL <= P; j += UNROLL) {
+            u32x4 th[UNROLL], tl[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                th[u] = HI_CACHED ? ph[(size_t)(j + u) * s8] : __builtin_nontemporal_load(ph + (size_t)(j + u) * s8);
+                tl[u] = __builtin_nontemporal_load(pl + (size_t)(j + u) * s8);
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) add(th[u], tl[u]);
+        }
+        for (; j < P; ++j)
+            add(HI_CACHED ? ph[(size_t)j * s8] : __builtin_nontemporal_load(ph + (size_t)j * s8),
+                __builtin_nontemporal_load(pl + (size_t)j * s8));
+        const f32x4 vo0 = ((const f32x4*)v)[2 * i], vo1 = ((const f32x4*)v)[2 * i + 1];
+        const float vo[8] = {vo0.x, vo0.y, vo0.z, vo0.w, vo1.x, vo1.y, vo1.z, vo1.w};
+        float vn[8], wn[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { vn[e] = mu * vo[e] + acc[e] * invP; wn[e] = wt[e] + vn[e]; }
+        ((f32x4*)v)[2 * i] = (f32x4){vn[0], vn[1], vn[2], vn[3]};
+        ((f32x4*)v)[2 * i + 1] = (f32x4){vn[4], vn[5], vn[6], vn[7]};
+        ((f32x4*)w_tilde)[2 * i] = (f32x4){wn[0], wn[1], wn[2], wn[3]};
+        ((f32x4*)w_tilde)[2 * i + 1] = (f32x4){wn[4], wn[5], wn[6], wn[7]};
+        u32x4 oh, ol;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t h2, l2;
+            split_pack2(__builtin_bit_cast(uint32_t, wn[2 * q]), __builtin_bit_cast(uint32_t, wn[2 * q + 1]), h2, l2);
+            oh[q] = h2; ol[q] = l2;
+        }
+        u32x4* qh = (u32x4*)hi + i;
+        u32x4* ql = (u32x4*)lo + i;
+        if (HI_CACHED) { for (int jj = 0; jj < P; ++jj) qh[(size_t)jj * s8] = oh; }
+        else { for (int jj = 0; jj < P; ++jj) __builtin_nontemporal_store(oh, qh + (size_t)jj * s8); }
+        for (int jj = 0; jj < P; ++jj) __builtin_nontemporal_store(ol, ql + (size_t)jj * s8);
+    } else {
+        const size_t e = 8 * n8 + (i - n8);               // ragged tail: at most 7 parameters
+        if (e < n) meta_split_scalar_element(w_tilde, v, hi, lo, stride, P, e, mu, invP);
+    }
+}
+
+hipError_t launch_meta_update_split(float* w_tilde, float* v, uint16_t* hi, uint16_t* lo, size_t stride,
+                                    int P, size_t n, float mu, int hi_cached, hipStream_t st) {
+    // planes and vectors come out of the 256-byte aligned workspace; stride is a multiple of 64
+    const float invP = 1.0f / (float)P;
+    const size_t n8 = n / 8;
+    const size_t threads = n8 + (n - 8 * n8);
+    const unsigned grid = (unsigned)((threads + 255) / 256);
+    if (hi_cached)
+        hipLaunchKernelGGL((meta_update_split_kernel<8, true>), dim3(grid), dim3(256), 0, st, w_tilde, v, hi, lo,
+                           stride, P, n8, n, mu, invP);
+    else
+        hipLaunchKernelGGL((meta_update_split_kernel<8, false>), dim3(grid), dim3(256), 0, st, w_tilde, v, hi, lo,
+                           stride, P, n8, n, mu, invP);
+    return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(256)
+broadcast_split_kernel(const float* __restrict__ w_tilde, uint16_t* __restrict__ hi, uint16_t* __restrict__ lo,
+                       size_t stride, int P, size_t n) {
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n) return;
+    const uint32_t b = __builtin_bit_cast(uint32_t, w_tilde[e]);
+    for (int j = 0; j < P; ++j) {
+        hi[(size_t)j * stride + e] = (uint16_t)split_hi(b);
+        lo[(size_t)j * stride + e] = (uint16_t)split_lo(b);
+    }
+}
+
+hipError_t launch_broadcast_split(const float* w_tilde, uint16_t* hi, uint16_t* lo, size_t stride, int P,
+                                  size_t n, hipStream_t st) {
+    const unsigned grid = (unsigned)((n + 255) / 256);
+    hipLaunchKernelGGL(broadcast_split_kernel, dim3(grid), dim3(256), 0, st, w_tilde, hi, lo, stride, P, n);
     return hipGetLastError();
 }
 

@@ -36,7 +36,7 @@ def gradient_fp32_accumulate(w, dims, Xb, yb, bf16=False):
     f32 = lambda a: np.asarray(a, dtype=np.float32)
     mm = lambda a, b: (f32(a) @ f32(b)).astype(np.float64)
     Ws, bs = O.unpack(w, dims)
-    Wq = [q(W) for W in Ws]
+    Wq = [(O.rna_bf16(W) if bf16 else W) for W in Ws]
     L = len(Ws)
     Zs, As = [], [Xb]
     for l in range(L):

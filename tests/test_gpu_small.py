@@ -112,7 +112,9 @@ def test_meta_update_flat_matches_oracle(P, n, shadow):
         assert np.array_equal(rg[:, :n], np.tile(w.cpu().numpy(), (P, 1)))
         assert np.all(rg[:, n:] == 0)                                 # padding untouched
         if shadow:
-            want_bits = synth.snap_to_bf16_grid(w.cpu().numpy())[0]
+            # the bf16 copies are the weights' rounding of the oracle: nearest, ties away from zero
+            want = O.rna_bf16(w.cpu().numpy().astype(np.float64)).astype(np.float32)
+            want_bits = (want.view(np.uint32) >> 16).astype(np.uint16)
             got_bits = sh.cpu().numpy().view(np.uint16)
             assert np.array_equal(got_bits[:, :n], np.tile(want_bits, (P, 1)))
 
