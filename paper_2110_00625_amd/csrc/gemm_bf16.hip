@@ -136,7 +136,8 @@ struct DirectLoader {
 };
 
 // Transposed operand: piece e covers memory row k0 + e/(X/8), columns x0 + 8*(e%(X/8)) .. +7.
-template <int X, int BK, int NT>
+// GATHER is a compile-time property: the plain path then contains no index loads and no waits.
+template <int X, int BK, int NT, bool GATHER>
 struct TransLoader {
     static constexpr int N = X * BK / 8 / NT;
     const uint16_t* colp;        // base + this thread's column offset; null: columns outside the operand
@@ -146,13 +147,32 @@ struct TransLoader {
         colp = x < o.n_cont ? base + x : nullptr;
         gather = g;
     }
+    // Gathered rows: all row indices of the slice are requested together, then all pieces, so there is
+    // one wait per slice (with the lookup inside one loop, every piece waited for its own index
+    // and, with it, for every older load).
     __device__ __forceinline__ void load(StageRegs<N>& g, const Operand& o, int k0, int tid) const {
+        if constexpr (GATHER) {
+            long row[N];
 #pragma unroll
-        for (int i = 0; i < N; ++i) {
-            const int k = k0 + (tid + NT * i) / (X / 8);
-            u32x4 val = {0u, 0u, 0u, 0u};
-            if (colp && k < o.n_rows) val = *(const u32x4*)(colp + (gather ? (long)gather[k] : (long)k) * o.ld);
-            g.v[i] = val;
+            for (int i = 0; i < N; ++i) {
+                const int k = k0 + (tid + NT * i) / (X / 8);
+                row[i] = gather[min(k, o.n_rows - 1)];
+            }
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                const int k = k0 + (tid + NT * i) / (X / 8);
+                u32x4 val = {0u, 0u, 0u, 0u};
+                if (colp && k < o.n_rows) val = *(const u32x4*)(colp + row[i] * o.ld);
+                g.v[i] = val;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                const int k = k0 + (tid + NT * i) / (X / 8);
+                u32x4 val = {0u, 0u, 0u, 0u};
+                if (colp && k < o.n_rows) val = *(const u32x4*)(colp + (long)k * o.ld);
+                g.v[i] = val;
+            }
         }
     }
     __device__ __forceinline__ void store(const StageRegs<N>& g, uint16_t* lds, int tid) const {
@@ -266,7 +286,8 @@ struct Shape {
 // summed through LDS at the end, in fixed order).  BK = slice length.  One slice is always in
 // flight in registers ahead of the one being multiplied; with PIPE_LDS2 the LDS tiles are double-buffered,
 // so the next slice is written while the current one is read and a slice costs one barrier, not two.
-template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RTRANS, bool CTRANS, int PIPE, bool SHADOW_CACHED = false>
+template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RTRANS, bool CTRANS, int PIPE, bool SHADOW_CACHED = false,
+          bool GATHER_C = false>
 __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
     constexpr int NW = WR * WC * WK, NT = 64 * NW;
     constexpr int MR = TR / (32 * WR), MC = TC / (32 * WC);
@@ -308,8 +329,8 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    DirectLoader<TR, BK, NT> rdl; TransLoader<TR, BK, NT> rtl;
-    DirectLoader<TC, BK, NT> cdl; TransLoader<TC, BK, NT> ctl;
+    DirectLoader<TR, BK, NT> rdl; TransLoader<TR, BK, NT, false> rtl;
+    DirectLoader<TC, BK, NT> cdl; TransLoader<TC, BK, NT, GATHER_C> ctl;
     if (RTRANS) rtl.init(a.R, Rbase, Rg, r0, tid); else rdl.init(a.R, Rbase, Rg, r0, tid);
     if (CTRANS) ctl.init(a.C, Cbase, Cg, c0, tid); else cdl.init(a.C, Cbase, Cg, c0, tid);
     StageRegs<TR * BK / 8 / NT> rg;
@@ -350,34 +371,12 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
         }
     };
 
-    // Update: the fp32 master tile is independent of the product, so its loads go out first and
-    // are in flight during the whole contraction (the kernel is bound by this stream, not by MFMAs).
-    // In the epilogue a lane owns eight consecutive columns of a row: 16 bytes of either plane.
+    // Update epilogue: a lane owns eight consecutive columns of a row, 16 bytes of either plane.
     constexpr int L8_PER_ROW = WTC / 8;
     constexpr int ROWS_PER_IT = 64 / L8_PER_ROW;
     constexpr int ITS = 32 / ROWS_PER_IT;
     u32x4 mhi[MODE == MODE_UPD ? MR : 1][MODE == MODE_UPD ? ITS : 1];
     u32x4 mlo[MODE == MODE_UPD ? MR : 1][MODE == MODE_UPD ? ITS : 1];
-    if (MODE == MODE_UPD) {
-        const uint16_t* hbase = a.ws + (size_t)learner * a.ws_lstride;
-        const uint16_t* lbase = a.wlo + (size_t)learner * a.ws_lstride;
-        const int c = c0 + wc * WTC + (lane % L8_PER_ROW) * 8;
-#pragma unroll
-        for (int i = 0; i < MR; ++i)
-#pragma unroll
-            for (int it = 0; it < ITS; ++it) {
-                const int r = r0 + (wr * MR + i) * 32 + it * ROWS_PER_IT + lane / L8_PER_ROW;
-                mhi[i][it] = (u32x4){0u, 0u, 0u, 0u};
-                mlo[i][it] = (u32x4){0u, 0u, 0u, 0u};
-                if (r < a.nR && c < a.nC) {
-                    // hi was left in the memory-side cache by the previous writer when it fits there
-                    // (otherwise it is streamed like lo, so as not to push anything else out)
-                    mhi[i][it] = SHADOW_CACHED ? *(const u32x4*)(hbase + (size_t)r * a.nC + c)
-                                               : __builtin_nontemporal_load((const u32x4*)(hbase + (size_t)r * a.nC + c));
-                    mlo[i][it] = __builtin_nontemporal_load((const u32x4*)(lbase + (size_t)r * a.nC + c));
-                }
-            }
-    }
 
     // What the epilogue reads from memory (bias of the lane's columns; ReLU mask of its outputs) is
     // requested here, ahead of the contraction, so that its latency is not paid after the last slice
@@ -435,24 +434,41 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
         __syncthreads();                                // tiles are dead: the k-group reduction reuses their LDS
     } else {
         fetch(0);
-        // Update of the first layer: the rows that the next local step samples are scattered over the data
-        // set, and its forward pass, with one slice of look-ahead, would pay the latency of such a read
-        // in every slice.  This launch is bound by its parameter stream and lasts long, so its
-        // workgroups touch those rows, one 128-byte line per lane (the learner's rows are spread over
-        // the learner's workgroups, which run on the XCD that will run its forward tiles).  The
-        // value is only kept alive until the end of the kernel.
-        if (MODE == MODE_UPD && a.next_gather) {
-            const int lines_per_row = (a.C.n_cont * 2 + 127) / 128;
-            const int lines = a.C.n_rows * lines_per_row;                 // of this learner
-            const int wgs = a.tiles_r * a.tiles_c;
-            const int per_wg = (lines + wgs - 1) / wgs;
-            const int32_t* ng = a.next_gather + (long)learner * a.C.gstride;
-            for (int t = tid; t < per_wg; t += NT) {
-                const int line = tile * per_wg + t;
-                if (line < lines) {
-                    const int row = line / lines_per_row, ln = line - row * lines_per_row;
-                    touched ^= *(const uint32_t*)(a.C.base + (long)ng[row] * a.C.ld + ln * 64);
+        if (MODE == MODE_UPD) {
+            // The master tile (both planes) is independent of the product: its loads go out right after
+            // the first operand slice and are in flight during the contraction.  They are issued
+            // without predicates (rows and columns beyond the layer are clamped; those lanes store
+            // nothing later), so that the compiler can count them: the wait for the operand slice is
+            // then "all but these", not "everything".
+            const uint16_t* hbase = a.ws + (size_t)learner * a.ws_lstride;
+            const uint16_t* lbase = a.wlo + (size_t)learner * a.ws_lstride;
+            const int c = min(c0 + wc * WTC + (lane % L8_PER_ROW) * 8, a.nC - 8);
+#pragma unroll
+            for (int i = 0; i < MR; ++i)
+#pragma unroll
+                for (int it = 0; it < ITS; ++it) {
+                    const int r = min(r0 + (wr * MR + i) * 32 + it * ROWS_PER_IT + lane / L8_PER_ROW, a.nR - 1);
+                    // hi was left in the memory-side cache by the previous writer when it fits there
+                    // (otherwise it is streamed like lo, so as not to push anything else out)
+                    mhi[i][it] = SHADOW_CACHED ? *(const u32x4*)(hbase + (size_t)r * a.nC + c)
+                                               : __builtin_nontemporal_load((const u32x4*)(hbase + (size_t)r * a.nC + c));
+                    mlo[i][it] = __builtin_nontemporal_load((const u32x4*)(lbase + (size_t)r * a.nC + c));
                 }
+            // Update of the first layer: the rows that the next local step samples are scattered over the
+            // data set, and its forward pass, with one slice of look-ahead, would pay the latency of such
+            // a read in every slice.  This launch lasts long, so its workgroups touch those rows, one
+            // 128-byte line per lane (the learner's rows are spread over the learner's workgroups, which
+            // run on the XCD that will run its forward tiles).  One unpredicated load per lane, again
+            // so that it can be counted; the value is only kept alive until the end of the kernel.
+            if (a.next_gather) {
+                const int lines_per_row = (a.C.n_cont * 2 + 127) / 128;
+                const int lines = a.C.n_rows * lines_per_row;                 // of this learner
+                const int wgs = a.tiles_r * a.tiles_c;
+                const int per_wg = min((lines + wgs - 1) / wgs, NT);          // beyond NT lines the rest stays untouched
+                const int32_t* ng = a.next_gather + (long)learner * a.C.gstride;
+                const int line = min(tile * per_wg + min(tid, per_wg - 1), lines - 1);
+                const int row = line / lines_per_row, ln = line - row * lines_per_row;
+                touched = *(const uint32_t*)(a.C.base + (long)ng[row] * a.C.ld + ln * 64);
             }
         }
         if (PIPE == PIPE_PLAIN) {
@@ -620,7 +636,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
     }
 }
 
-template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RT, bool CT, int PIPE, bool SC = false>
+template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RT, bool CT, int PIPE, bool SC = false, bool GC = false>
 hipError_t launch(Args a, int P, hipStream_t st) {
     a.tiles_c = (a.nC + TC - 1) / TC;
     a.tiles_r = (a.nR + TR - 1) / TR;
@@ -631,11 +647,11 @@ hipError_t launch(Args a, int P, hipStream_t st) {
     static_assert(SMEM <= 160 * 1024, "more LDS than a compute unit has");
     if (SMEM > 64 * 1024) {                     // beyond the default limit: raise it once for this kernel
         static hipError_t raised = hipFuncSetAttribute(
-            (const void*)gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE, SC>,
+            (const void*)gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE, SC, GC>,
             hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
         if (raised != hipSuccess) return raised;
     }
-    hipLaunchKernelGGL((gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE, SC>), grid, dim3(64 * WR * WC * WK),
+    hipLaunchKernelGGL((gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE, SC, GC>), grid, dim3(64 * WR * WC * WK),
                        SMEM, st, a);
     return hipGetLastError();
 }
@@ -706,8 +722,12 @@ hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     a.next_gather = c.gather ? c.next_gather : nullptr;
     // Tile shapes from measured sweeps (whole rounds, same box): 64x64 where the shadows stay cached
     // (CIFAR-MLP: +2 % over 128x128), 64x128 where they stream (the 4096-wide workloads: +3 %).
-    if (c.shadow_cached) return launch<MODE_UPD, 128, 64, 4, 1, 1, 64, true, true, PIPE_PLAIN, true>(a, c.P, st);
-    return launch<MODE_UPD, 64, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false>(a, c.P, st);
+    if (c.shadow_cached) {
+        if (c.gather) return launch<MODE_UPD, 128, 64, 4, 1, 1, 64, true, true, PIPE_PLAIN, true, true>(a, c.P, st);
+        return launch<MODE_UPD, 128, 64, 4, 1, 1, 64, true, true, PIPE_PLAIN, true, false>(a, c.P, st);
+    }
+    if (c.gather) return launch<MODE_UPD, 64, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, true>(a, c.P, st);
+    return launch<MODE_UPD, 64, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, false>(a, c.P, st);
 }
 
 }  // namespace kavg
