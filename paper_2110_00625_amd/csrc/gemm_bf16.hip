@@ -140,46 +140,52 @@ struct DirectLoader {
 template <int X, int BK, int NT, bool GATHER>
 struct TransLoader {
     static constexpr int N = X * BK / 8 / NT;
-    const uint16_t* colp;        // base + this thread's column offset; null: columns outside the operand
+    const uint16_t* colp;        // base + this thread's (clamped) column offset
     const int32_t* gather;
+    bool col_ok;                 // the thread's columns lie inside the operand
+    unsigned row_ok;             // bit i: piece i of the slice in the registers lies inside the operand
+    int32_t next_row[GATHER ? N : 1];   // gathered rows of the slice that the next load() fetches
+    __device__ __forceinline__ void lookup(const Operand& o, int k0, int tid) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int k = k0 + (tid + NT * i) / (X / 8);
+            if constexpr (GATHER) next_row[i] = gather[min(k, o.n_rows - 1)];
+        }
+    }
     __device__ __forceinline__ void init(const Operand& o, const uint16_t* base, const int32_t* g, int x0, int tid) {
         const int x = x0 + (tid % (X / 8)) * 8;      // NT is a multiple of X/8: same column for every piece
-        colp = x < o.n_cont ? base + x : nullptr;
+        col_ok = x < o.n_cont;
+        colp = base + min(x, o.n_cont - 8);
         gather = g;
+        row_ok = 0;
+        lookup(o, 0, tid);
     }
-    // Gathered rows: all row indices of the slice are requested together, then all pieces, so there is
-    // one wait per slice (with the lookup inside one loop, every piece waited for its own index
-    // and, with it, for every older load).
-    __device__ __forceinline__ void load(StageRegs<N>& g, const Operand& o, int k0, int tid) const {
-        if constexpr (GATHER) {
-            long row[N];
+    // No load is predicated: rows and columns outside the operand are clamped to valid addresses and
+    // the piece is replaced by zeros on its way to LDS.  Without branches around the loads the
+    // compiler can count how many are outstanding, so a wait for this slice does not have to be a
+    // wait for every load issued since.  Gathered rows are looked up one slice ahead (init for the first
+    // slice, each load() for the following one), so the wait for them is a wait for old loads only.
+    // Slices are fetched in ascending order, BK apart.
+    __device__ __forceinline__ void load(StageRegs<N>& g, const Operand& o, int k0, int tid) {
+        long row[N];
+        row_ok = 0;
 #pragma unroll
-            for (int i = 0; i < N; ++i) {
-                const int k = k0 + (tid + NT * i) / (X / 8);
-                row[i] = gather[min(k, o.n_rows - 1)];
-            }
-#pragma unroll
-            for (int i = 0; i < N; ++i) {
-                const int k = k0 + (tid + NT * i) / (X / 8);
-                u32x4 val = {0u, 0u, 0u, 0u};
-                if (colp && k < o.n_rows) val = *(const u32x4*)(colp + row[i] * o.ld);
-                g.v[i] = val;
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < N; ++i) {
-                const int k = k0 + (tid + NT * i) / (X / 8);
-                u32x4 val = {0u, 0u, 0u, 0u};
-                if (colp && k < o.n_rows) val = *(const u32x4*)(colp + (long)k * o.ld);
-                g.v[i] = val;
-            }
+        for (int i = 0; i < N; ++i) {
+            const int k = k0 + (tid + NT * i) / (X / 8);
+            if (k < o.n_rows) row_ok |= 1u << i;
+            row[i] = GATHER ? (long)next_row[i] : (long)min(k, o.n_rows - 1);
         }
+        lookup(o, k0 + BK, tid);
+#pragma unroll
+        for (int i = 0; i < N; ++i) g.v[i] = *(const u32x4*)(colp + row[i] * o.ld);
     }
     __device__ __forceinline__ void store(const StageRegs<N>& g, uint16_t* lds, int tid) const {
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             const int e = tid + NT * i;
-            *(u32x4*)(lds + (e / (X / 8)) * tpitch(X) + (e % (X / 8)) * 8) = g.v[i];
+            const u32x4 zero = {0u, 0u, 0u, 0u};
+            const bool ok = col_ok && ((row_ok >> i) & 1u);
+            *(u32x4*)(lds + (e / (X / 8)) * tpitch(X) + (e % (X / 8)) * 8) = ok ? g.v[i] : zero;
         }
     }
 };
@@ -433,8 +439,29 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
         }
         __syncthreads();                                // tiles are dead: the k-group reduction reuses their LDS
     } else {
+        // Update of the first layer: the rows that the next local step samples are scattered over the data
+        // set, and its forward pass, with one slice of look-ahead, would pay the latency of such a read in
+        // every slice.  This launch lasts long, so its workgroups touch those rows, one 128-byte line
+        // per lane (the learner's rows are spread over the learner's workgroups, which run on the XCD
+        // that will run its forward tiles).  One unpredicated load per lane, so that it can be
+        // counted; its row index is looked up first of all, so that waiting for the index does not
+        // mean waiting for the loads below; the value is only kept alive until the end of the kernel.
+        // Without a next step, or without a gather, the line touched is one of this launch's own operand.
+        const uint32_t* touch_at = nullptr;
+        if (MODE == MODE_UPD) {
+            const int lines_per_row = (a.C.n_cont * 2 + 127) / 128;
+            const int lines = a.C.n_rows * lines_per_row;                 // of this learner
+            const int wgs = a.tiles_r * a.tiles_c;
+            const int per_wg = min((lines + wgs - 1) / wgs, NT);          // beyond NT lines the rest stays untouched
+            const int line = min(tile * per_wg + min(tid, per_wg - 1), lines - 1);
+            const int row = line / lines_per_row, ln = line - row * lines_per_row;
+            long mrow = row;
+            if constexpr (GATHER_C) mrow = ((a.next_gather ? a.next_gather : a.C.gather) + (long)learner * a.C.gstride)[row];
+            touch_at = (const uint32_t*)(Cbase + mrow * a.C.ld + ln * 64);
+        }
         fetch(0);
         if (MODE == MODE_UPD) {
+            __builtin_amdgcn_sched_barrier(0);          // keep the operand loads the oldest
             // The master tile (both planes) is independent of the product: its loads go out right after
             // the first operand slice and are in flight during the contraction.  They are issued
             // without predicates (rows and columns beyond the layer are clamped; those lanes store
@@ -454,25 +481,11 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                                                : __builtin_nontemporal_load((const u32x4*)(hbase + (size_t)r * a.nC + c));
                     mlo[i][it] = __builtin_nontemporal_load((const u32x4*)(lbase + (size_t)r * a.nC + c));
                 }
-            // Update of the first layer: the rows that the next local step samples are scattered over the
-            // data set, and its forward pass, with one slice of look-ahead, would pay the latency of such
-            // a read in every slice.  This launch lasts long, so its workgroups touch those rows, one
-            // 128-byte line per lane (the learner's rows are spread over the learner's workgroups, which
-            // run on the XCD that will run its forward tiles).  One unpredicated load per lane, again
-            // so that it can be counted; the value is only kept alive until the end of the kernel.
-            if (a.next_gather) {
-                const int lines_per_row = (a.C.n_cont * 2 + 127) / 128;
-                const int lines = a.C.n_rows * lines_per_row;                 // of this learner
-                const int wgs = a.tiles_r * a.tiles_c;
-                const int per_wg = min((lines + wgs - 1) / wgs, NT);          // beyond NT lines the rest stays untouched
-                const int32_t* ng = a.next_gather + (long)learner * a.C.gstride;
-                const int line = min(tile * per_wg + min(tid, per_wg - 1), lines - 1);
-                const int row = line / lines_per_row, ln = line - row * lines_per_row;
-                touched = *(const uint32_t*)(a.C.base + (long)ng[row] * a.C.ld + ln * 64);
-            }
+            __builtin_amdgcn_sched_barrier(0);
+            touched = *touch_at;
         }
         if (PIPE == PIPE_PLAIN) {
-            for (int k0 = 0; k0 < a.nK; k0 += BK) {
+            auto slice = [&](int k0) {
                 stash(0);
                 __syncthreads();
                 if (k0 + BK < a.nK) fetch(k0 + BK);     // next slice in flight during the MFMAs
@@ -483,7 +496,11 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                     for (int k = 0; k < BK; ++k) bias_sum += bf16_to_f32(Rs[k * tpitch(TR) + tid]);
                 }
                 __syncthreads();
-            }
+            };
+            // The first slice stands outside the loop: there the compiler knows that the operand loads
+            // are the oldest outstanding ones and waits only for them, not for the master tile.
+            slice(0);
+            for (int k0 = BK; k0 < a.nK; k0 += BK) slice(k0);
         } else {
             stash(0);
             __syncthreads();
