@@ -393,9 +393,18 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
         const uint16_t* bh = a.bias_hi + (size_t)learner * a.bias_lstride;
         const uint16_t* bl = a.bias_lo + (size_t)learner * a.bias_lstride;
         const int c = c0 + (wc * MC + j) * 32 + q * 8 + (lane >> 5) * 4;
-        auto one = [&](int cc) { return cc < a.nC ? __builtin_bit_cast(float, split_join(bh[cc], bl[cc])) : 0.f; };
         f32x4 b;
-        b.x = one(c + 0); b.y = one(c + 1); b.z = one(c + 2); b.w = one(c + 3);
+        if (c + 4 <= a.nC) {                      // four columns at once (the planes are 8-byte aligned there)
+            const u32x2 h = *(const u32x2*)(bh + c), l = *(const u32x2*)(bl + c);
+            uint32_t b0, b1, b2, b3;
+            split_join2(h.x, l.x, b0, b1);
+            split_join2(h.y, l.y, b2, b3);
+            b = (f32x4){__builtin_bit_cast(float, b0), __builtin_bit_cast(float, b1),
+                        __builtin_bit_cast(float, b2), __builtin_bit_cast(float, b3)};
+        } else {
+            auto one = [&](int cc) { return cc < a.nC ? __builtin_bit_cast(float, split_join(bh[cc], bl[cc])) : 0.f; };
+            b.x = one(c + 0); b.y = one(c + 1); b.z = one(c + 2); b.w = one(c + 3);
+        }
         return b;
     };
     auto mask_of = [&](int i, int j, int q) {
