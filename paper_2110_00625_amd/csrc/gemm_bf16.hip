@@ -389,23 +389,29 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
     // -- for single-block wavefront tiles only: with more blocks the extra registers cost occupancy.
     // Only the wavefronts of k group 0 reach the epilogue.
     constexpr bool EARLY = MR * MC == 1;
-    auto bias_of = [&](int j, int q) {
+    // bias of four columns: raw hi / lo words (requested early, joined only where they are used: joining
+    // at once would make every request wait for its own answer)
+    auto bias_raw = [&](int j, int q, u32x2& h, u32x2& l) {
         const uint16_t* bh = a.bias_hi + (size_t)learner * a.bias_lstride;
         const uint16_t* bl = a.bias_lo + (size_t)learner * a.bias_lstride;
         const int c = c0 + (wc * MC + j) * 32 + q * 8 + (lane >> 5) * 4;
-        f32x4 b;
+        h = (u32x2){0u, 0u}; l = (u32x2){0u, 0u};
         if (c + 4 <= a.nC) {                      // four columns at once (the planes are 8-byte aligned there)
-            const u32x2 h = *(const u32x2*)(bh + c), l = *(const u32x2*)(bl + c);
-            uint32_t b0, b1, b2, b3;
-            split_join2(h.x, l.x, b0, b1);
-            split_join2(h.y, l.y, b2, b3);
-            b = (f32x4){__builtin_bit_cast(float, b0), __builtin_bit_cast(float, b1),
-                        __builtin_bit_cast(float, b2), __builtin_bit_cast(float, b3)};
-        } else {
-            auto one = [&](int cc) { return cc < a.nC ? __builtin_bit_cast(float, split_join(bh[cc], bl[cc])) : 0.f; };
-            b.x = one(c + 0); b.y = one(c + 1); b.z = one(c + 2); b.w = one(c + 3);
+            h = *(const u32x2*)(bh + c); l = *(const u32x2*)(bl + c);
+        } else {                                  // ragged end: column by column, zeros beyond the layer
+            uint32_t hv[4] = {0u, 0u, 0u, 0u}, lv[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) if (c + e < a.nC) { hv[e] = bh[c + e]; lv[e] = bl[c + e]; }
+            h = (u32x2){hv[0] | (hv[1] << 16), hv[2] | (hv[3] << 16)};
+            l = (u32x2){lv[0] | (lv[1] << 16), lv[2] | (lv[3] << 16)};
         }
-        return b;
+    };
+    auto bias_join = [&](const u32x2& h, const u32x2& l) {
+        uint32_t b0, b1, b2, b3;
+        split_join2(h.x, l.x, b0, b1);
+        split_join2(h.y, l.y, b2, b3);
+        return (f32x4){__builtin_bit_cast(float, b0), __builtin_bit_cast(float, b1),
+                       __builtin_bit_cast(float, b2), __builtin_bit_cast(float, b3)};
     };
     auto mask_of = [&](int i, int j, int q) {
         const int r = r0 + (wr * MR + i) * 32 + (lane & 31);
@@ -415,12 +421,12 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
             m = *(const u32x2*)(a.act_prev + (size_t)learner * a.act_lstride + (size_t)r * a.ld_act + c);
         return m;
     };
-    f32x4 ebias[4];
+    u32x2 ebh[4], ebl[4];
     u32x2 emask[4];
     if (EARLY && wk == 0) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            if (MODE == MODE_FWD) ebias[q] = bias_of(0, q);
+            if (MODE == MODE_FWD) bias_raw(0, q, ebh[q], ebl[q]);
             if (MODE == MODE_BWD) emask[q] = mask_of(0, 0, q);
         }
     }
@@ -570,7 +576,9 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                     float v2 = acc[i][j][4 * q + 2], v3 = acc[i][j][4 * q + 3];
                     if (MODE == MODE_FWD) {
                         if (c >= a.ld_out) continue;
-                        const f32x4 bq = EARLY ? ebias[q] : bias_of(j, q);
+                        u32x2 bh2, bl2;
+                        if (EARLY) { bh2 = ebh[q]; bl2 = ebl[q]; } else bias_raw(j, q, bh2, bl2);
+                        const f32x4 bq = bias_join(bh2, bl2);
                         v0 += bq.x; v1 += bq.y; v2 += bq.z; v3 += bq.w;
                         if (a.relu) {
                             u32x2 o = {pack2(fmaxf(v0, 0.f), fmaxf(v1, 0.f)), pack2(fmaxf(v2, 0.f), fmaxf(v3, 0.f))};
