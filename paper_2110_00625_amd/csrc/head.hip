@@ -28,8 +28,33 @@ constexpr int CMAX = 16;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// Data-parallel-primitive moves inside a row of 16 lanes: no LDS round trip, unlike a general shuffle.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
+}
+// Sum over the 64 lanes, the same value in every lane.  Inside a row: neighbours, pairs, mirrored halves,
+// mirrored row (every lane then holds its row's sum); across the four rows: their last lanes are read
+// as scalars and added in a fixed order.
 __device__ __forceinline__ float wave_sum(float x) {
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    x += dpp_move<0xB1>(x);        // quad_perm [1,0,3,2]
+    x += dpp_move<0x4E>(x);        // quad_perm [2,3,0,1]
+    x += dpp_move<0x141>(x);       // row_half_mirror
+    x += dpp_move<0x140>(x);       // row_mirror
+    const int xi = __builtin_bit_cast(int, x);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 15));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 31));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 47));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 63));
+    return (r0 + r1) + (r2 + r3);
+}
+// Sum over the 16 lanes that differ in bits 2..5 of the lane index (same low two bits), in every lane:
+// rotations by 4 and 8 inside a row keep the low bits; the rows are joined by two shuffles.
+__device__ __forceinline__ float groups_sum(float x) {
+    x += dpp_move<0x124>(x);       // row_ror:4
+    x += dpp_move<0x128>(x);       // row_ror:8
+    x += __shfl_xor(x, 16, 64);
+    x += __shfl_xor(x, 32, 64);
     return x;
 }
 __device__ __forceinline__ uint16_t bf16_bits(float x) {
@@ -251,16 +276,11 @@ __global__ void __launch_bounds__(256) head_update_kernel(HeadArgs a) {
 #pragma unroll
     for (int c = 0; c < CT; ++c) {
         float b = bsum[c];
-        b += __shfl_xor(b, 4, 64); b += __shfl_xor(b, 8, 64); b += __shfl_xor(b, 16, 64); b += __shfl_xor(b, 32, 64);
-        bsum[c] = b;
+        bsum[c] = groups_sum(b);
 #pragma unroll
         for (int e = 0; e < N; ++e) {
             float v = acc[c][e];
-            v += __shfl_xor(v, 4, 64);
-            v += __shfl_xor(v, 8, 64);
-            v += __shfl_xor(v, 16, 64);
-            v += __shfl_xor(v, 32, 64);
-            acc[c][e] = v;
+            acc[c][e] = groups_sum(v);
         }
     }
     if (live && grp < a.C) {
