@@ -65,24 +65,32 @@ __device__ __forceinline__ float bf16_round(float x) {
     return __builtin_bit_cast(float, (uint32_t)bf16_bits(x) << 16);
 }
 
-// A "piece" is what one lane loads at once: 8 bf16 or 1 float.
+// A "piece" is what one lane loads at once: 8 bf16 or 1 float.  It is kept as loaded (r) and unpacked
+// into floats (v) only where it is used, so that pieces can stay in registers cheaply.
 template <bool BF16> struct Piece;
 template <> struct Piece<true> {
     static constexpr int N = 8;
+    u32x4 r;
     float v[8];
-    __device__ __forceinline__ void load(const void* base, size_t elem) {
-        const u32x4 r = *(const u32x4*)((const uint16_t*)base + elem);
+    __device__ __forceinline__ void fetch(const void* base, size_t elem) { r = *(const u32x4*)((const uint16_t*)base + elem); }
+    __device__ __forceinline__ void clear() { r = (u32x4){0u, 0u, 0u, 0u}; }
+    __device__ __forceinline__ void unpack() {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             v[2 * i] = __builtin_bit_cast(float, r[i] << 16);
             v[2 * i + 1] = __builtin_bit_cast(float, r[i] & 0xFFFF0000u);
         }
     }
+    __device__ __forceinline__ void load(const void* base, size_t elem) { fetch(base, elem); unpack(); }
 };
 template <> struct Piece<false> {
     static constexpr int N = 1;
+    float r;
     float v[1];
-    __device__ __forceinline__ void load(const void* base, size_t elem) { v[0] = ((const float*)base)[elem]; }
+    __device__ __forceinline__ void fetch(const void* base, size_t elem) { r = ((const float*)base)[elem]; }
+    __device__ __forceinline__ void clear() { r = 0.f; }
+    __device__ __forceinline__ void unpack() { v[0] = r; }
+    __device__ __forceinline__ void load(const void* base, size_t elem) { fetch(base, elem); unpack(); }
 };
 
 struct HeadArgs {
@@ -105,7 +113,9 @@ struct HeadArgs {
 // CT = compile-time bound on the class count (4, 8, 12 or 16): every loop over classes is fully
 // unrolled and its loads are issued unconditionally (rows beyond C re-read row C-1 and are ignored),
 // so that a lane's loads of a step go out together instead of one round trip per class.
-template <bool BF16, int CT>
+// KEEP: the row has at most 128 pieces (two per lane); they are fetched once and stay in registers for
+// the second pass (the data gradient) instead of being fetched again.
+template <bool BF16, int CT, bool KEEP>
 __global__ void __launch_bounds__(256) head_forward_backward_kernel(HeadArgs a) {
     constexpr int N = Piece<BF16>::N;
     const int lane = threadIdx.x & 63;
@@ -138,15 +148,38 @@ __global__ void __launch_bounds__(256) head_forward_backward_kernel(HeadArgs a) 
     float acc[CT];
 #pragma unroll
     for (int c = 0; c < CT; ++c) acc[c] = 0.f;
-    for (int q = lane; q < pieces; q += 64) {
-        Piece<BF16> x, w[CT];
-        x.load(a.act, arow + (size_t)q * N);
+    Piece<BF16> xs[KEEP ? 2 : 1], ws[CT][KEEP ? 2 : 1];
+    if constexpr (KEEP) {
 #pragma unroll
-        for (int c = 0; c < CT; ++c) w[c].load(W, wrow[c] + (size_t)q * N);
+        for (int it = 0; it < 2; ++it) {
+            const int q = lane + 64 * it;
+            const size_t qq = (size_t)(q < pieces ? q : pieces - 1) * N;      // clamped: no predicated loads
+            xs[it].fetch(a.act, arow + qq);
 #pragma unroll
-        for (int c = 0; c < CT; ++c)
+            for (int c = 0; c < CT; ++c) ws[c][it].fetch(W, wrow[c] + qq);
+        }
 #pragma unroll
-            for (int e = 0; e < N; ++e) acc[c] = fmaf(x.v[e], w[c].v[e], acc[c]);
+        for (int it = 0; it < 2; ++it) {
+            if (lane + 64 * it >= pieces) xs[it].clear();                      // contributes nothing to either pass
+            xs[it].unpack();
+#pragma unroll
+            for (int c = 0; c < CT; ++c) {
+                ws[c][it].unpack();
+#pragma unroll
+                for (int e = 0; e < N; ++e) acc[c] = fmaf(xs[it].v[e], ws[c][it].v[e], acc[c]);
+            }
+        }
+    } else {
+        for (int q = lane; q < pieces; q += 64) {
+            Piece<BF16> x, w[CT];
+            x.load(a.act, arow + (size_t)q * N);
+#pragma unroll
+            for (int c = 0; c < CT; ++c) w[c].load(W, wrow[c] + (size_t)q * N);
+#pragma unroll
+            for (int c = 0; c < CT; ++c)
+#pragma unroll
+                for (int e = 0; e < N; ++e) acc[c] = fmaf(x.v[e], w[c].v[e], acc[c]);
+        }
     }
     float mx = -INFINITY;
 #pragma unroll
@@ -182,11 +215,7 @@ __global__ void __launch_bounds__(256) head_forward_backward_kernel(HeadArgs a) 
     if (!a.dz_prev) return;
 
     // dZ_{L-1}[s][k] = (sum_c dZ_L[s][c] W_L[c][k]) * [A_{L-1}[s][k] > 0]      (gz[c] = 0 beyond C)
-    for (int q = lane; q < pieces; q += 64) {
-        Piece<BF16> x, w[CT];
-        x.load(a.act, arow + (size_t)q * N);
-#pragma unroll
-        for (int c = 0; c < CT; ++c) w[c].load(W, wrow[c] + (size_t)q * N);
+    auto data_gradient = [&](int q, Piece<BF16>& x, Piece<BF16> (&w)[CT]) {
         float da[N];
 #pragma unroll
         for (int e = 0; e < N; ++e) da[e] = 0.f;
@@ -204,6 +233,27 @@ __global__ void __launch_bounds__(256) head_forward_backward_kernel(HeadArgs a) 
             *(u32x4*)((uint16_t*)a.dz_prev + at) = o;
         } else {
             ((float*)a.dz_prev)[at] = da[0];
+        }
+    };
+    if constexpr (KEEP) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int q = lane + 64 * it;
+            if (q < pieces) {
+                Piece<BF16> w[CT];
+#pragma unroll
+                for (int c = 0; c < CT; ++c) { w[c] = ws[c][it]; w[c].unpack(); }
+                xs[it].unpack();
+                data_gradient(q, xs[it], w);
+            }
+        }
+    } else {
+        for (int q = lane; q < pieces; q += 64) {
+            Piece<BF16> x, w[CT];
+            x.load(a.act, arow + (size_t)q * N);
+#pragma unroll
+            for (int c = 0; c < CT; ++c) w[c].load(W, wrow[c] + (size_t)q * N);
+            data_gradient(q, x, w);
         }
     }
 }
@@ -360,12 +410,17 @@ HeadArgs make_args(const LayerCall& c, const int32_t* y, const int32_t* idx, lon
 bool head_supported(int C) { return C <= CMAX; }
 
 namespace {
+template <bool BF16, bool KEEP>
+void launch_fb2(const HeadArgs& a, dim3 grid, hipStream_t st) {
+    if (a.C <= 4) hipLaunchKernelGGL((head_forward_backward_kernel<BF16, 4, KEEP>), grid, dim3(256), 0, st, a);
+    else if (a.C <= 8) hipLaunchKernelGGL((head_forward_backward_kernel<BF16, 8, KEEP>), grid, dim3(256), 0, st, a);
+    else if (a.C <= 12) hipLaunchKernelGGL((head_forward_backward_kernel<BF16, 12, KEEP>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((head_forward_backward_kernel<BF16, 16, KEEP && !BF16>), grid, dim3(256), 0, st, a);   // bf16 x 16 classes: too many registers to keep
+}
 template <bool BF16>
 void launch_fb(const HeadArgs& a, dim3 grid, hipStream_t st) {
-    if (a.C <= 4) hipLaunchKernelGGL((head_forward_backward_kernel<BF16, 4>), grid, dim3(256), 0, st, a);
-    else if (a.C <= 8) hipLaunchKernelGGL((head_forward_backward_kernel<BF16, 8>), grid, dim3(256), 0, st, a);
-    else if (a.C <= 12) hipLaunchKernelGGL((head_forward_backward_kernel<BF16, 12>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((head_forward_backward_kernel<BF16, 16>), grid, dim3(256), 0, st, a);
+    const int pieces = a.d / Piece<BF16>::N;
+    if (pieces <= 128) launch_fb2<BF16, true>(a, grid, st); else launch_fb2<BF16, false>(a, grid, st);
 }
 template <bool BF16>
 void launch_upd(const HeadArgs& a, dim3 grid, hipStream_t st) {
