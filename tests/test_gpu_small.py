@@ -464,3 +464,29 @@ def test_graph_needs_a_stream_of_its_own():
     g.local_steps()                                      # the context keeps working eagerly
     g.graph(False)
     g.close()
+
+
+# ----------------------------------------------------------------- split storage of the fp32 master
+def test_split_storage_returns_every_fp32_pattern_exactly():
+    """Mixed precision keeps a learner's fp32 parameters as a bf16 plane plus a 16-bit remainder plane.
+    Whatever fp32 values go in must come back bit for bit: ties of the bf16 rounding in both signs,
+    remainders just below and above one half, carries into the exponent, zeros, tiny and large values."""
+    dims, P = (40, 24, 6), 3
+    n = kavg.kavg_num_params(dims)
+    rng = np.random.default_rng(7)
+    bits = rng.integers(0, 1 << 32, size=n, dtype=np.uint64).astype(np.uint32)
+    bits &= np.uint32(0xBFFFFFFF)                              # keep exponents away from inf / nan
+    special = np.array([0x3F808000, 0xBF808000, 0x3F818000, 0xBF818000, 0x3F807FFF, 0x3F808001,
+                        0x3FFFFFFF, 0xBFFFFFFF, 0x3FFF8000, 0x00000000, 0x80000000, 0x00800000,
+                        0x3F800000, 0x3F80FFFF, 0x7F000000 & 0x7EFFFFFF, 0x0000FFFF, 0x00008000], dtype=np.uint32)
+    bits[:special.size] = special
+    w0 = bits.view(np.float32).copy()
+    data = _dataset(64, dims, True, 3)
+    g = kavg.MAvg(P, 2, 0.0, 0.5, dims, 8, kavg.KAVG_BF16, index_seed=1)
+    X, y = _to_device(data, True)
+    g.set_data(X, y)
+    g.set_params(w0)
+    for j in range(P):
+        assert np.array_equal(g.replica(j).view(np.uint32), bits), "replica %d after set_params" % j
+    assert np.array_equal(g.params().view(np.uint32), bits)
+    g.close()
