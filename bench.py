@@ -208,9 +208,9 @@ def main():
     heavy = max(("forward", "backward", "update", "meta"), key=lambda c: breakdown[c][0])
 
     # timed region: only the dominant class carries events, and only one launch in EVERY of it
-    # (an event pair costs ~10 us of stream time; 7 is coprime with the launches per round, so
+    # (an event pair costs ~10 us of stream time; 17 is coprime with the launches per round, so
     # the sample walks evenly over the layers)
-    EVERY = 7
+    EVERY = 17
     g.profile([heavy], every=EVERY)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
