@@ -10,7 +10,8 @@
 //   backward-data  r = sample, c = input unit,  k = output unit
 //                  dZ_{l-1} = bf16((dZ_l W_l) * [A_{l-1} > 0])
 //   update         r = output unit, c = input unit, k = sample
-//                  W_l <- W_l - lr * dZ_l^T A_{l-1}  on the fp32 master, bf16 shadow refreshed,
+//                  W_l <- W_l - lr * dZ_l^T A_{l-1}  on the fp32 master (stored as two 16-bit
+//                  planes, split.h: the bf16 plane is what the other two products read),
 //                  b_l <- b_l - lr * colsum(dZ_l)
 //                  (the learner update of Algorithm 1; the 1/B factor already sits in dZ_L)
 //
@@ -29,7 +30,10 @@
 // (ds_read_b64_tr_b16): inside a 16-lane group the lanes fetch a 4(k) x 16(x)
 // block, four consecutive x per lane, and each lane receives the four k of
 // one x.  Both LDS layouts are padded so that fragment reads and tile writes
-// spread over all banks.
+// spread over all banks.  The forward pass (both operands direct) skips the
+// registers: its slices go from global memory straight into LDS
+// (global_load_lds_dwordx4), unpadded, with the 16-byte chunks of a row permuted
+// instead (DmaLoader).
 //
 // Rows beyond an extent are zero-filled on load and masked on store; every
 // memory-contiguous extent is a multiple of 8 elements (hidden widths are
