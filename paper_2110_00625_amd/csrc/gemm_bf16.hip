@@ -765,8 +765,9 @@ hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     a.ws = c.ws; a.wlo = c.wlo; a.ws_lstride = c.ws_stride; a.bhi = c.bhi; a.blo = c.blo; a.w_lstride = c.w_stride;
     a.lr = c.lr; a.u = c.u; a.ub = c.ub; a.beta = c.beta;
     a.next_gather = c.gather ? c.next_gather : nullptr;
-    // Tile shapes from measured sweeps (whole rounds, same box): 64x64 where the shadows stay cached
-    // (CIFAR-MLP: +2 % over 128x128), 64x128 where they stream (the 4096-wide workloads: +3 %).
+    // Tile shapes from measured sweeps (whole rounds, same box): wavefront tiles of 32x64 in both regimes
+    // (128-byte row segments per plane), as 128x64 where the bf16 planes stay in the memory-side
+    // cache (CIFAR-MLP) and as 64x128 where they stream (the 4096-wide workloads).
     if (c.shadow_cached) {
         if (c.gather) return launch<MODE_UPD, 128, 64, 4, 1, 1, 64, true, true, PIPE_PLAIN, true, true>(a, c.P, st);
         return launch<MODE_UPD, 128, 64, 4, 1, 1, 64, true, true, PIPE_PLAIN, true, false>(a, c.P, st);

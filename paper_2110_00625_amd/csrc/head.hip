@@ -16,7 +16,8 @@
 // Mixed precision follows the same rounding points as the generic kernels:
 // products of bf16 operands accumulated in fp32, dZ_L and dZ_{L-1} rounded to
 // bf16 (round to nearest even) before any use, logits / softmax / loss / bias
-// / master update in fp32, shadow refreshed from the updated master.
+// / master update in fp32; the master is read and written as its two 16-bit
+// planes (split.h), of which the bf16 one is the operand of the products.
 #include "kavg_internal.h"
 #include "split.h"
 
@@ -96,7 +97,7 @@ template <> struct Piece<false> {
 struct HeadArgs {
     const void* act; int ld_act; size_t act_lstride;      // A_{L-1} [P][B][ld_act], or the data set when gather != null
     const int32_t* gather; long gather_lstride;           // row s of learner j is data row gather[j*gather_lstride + s]
-    const void* wmul; size_t wmul_lstride;                // weights as multiplied: bf16 shadow or fp32 master, [C][d]
+    const void* wmul; size_t wmul_lstride;                // weights as multiplied: bf16 (hi) plane or fp32, [C][d]
     float* wmaster; size_t w_lstride;                     // fp32 mode: the layer's weights
     float* bias;                                          // fp32 mode: its bias (stride w_lstride)
     uint16_t* whi; uint16_t* wlo; size_t ws_lstride;      // bf16 mode: hi / lo planes of the weights (split.h)

@@ -205,7 +205,7 @@ struct Bracket {
     ~Bracket() { if (on) (void)hipEventRecord(stop, c->stream); }
 };
 
-// The bf16 shadows of all learners are re-read by every forward pass.  If together they fit well
+// The bf16 (hi) planes of all learners are re-read by every forward pass.  If together they fit well
 // inside the memory-side cache of the chip (256 MB), the kernels that write them use ordinary
 // stores and the next reader finds them there; larger sets are written with streaming stores,
 // which measured faster than letting them churn the cache.

@@ -53,7 +53,7 @@ struct LayerCall {
     uint16_t* ws;   size_t ws_stride;     // hi plane of the weights (first learner), else null
     uint16_t* wlo;                          // lo plane of the weights (stride ws_stride)
     uint16_t* bhi;  uint16_t* blo;          // hi / lo planes of the bias (stride ws_stride)
-    int shadow_cached;                    // updates store the shadow with ordinary (1) or streaming (0) stores
+    int shadow_cached;                    // updates access the bf16 (hi) plane with ordinary (1) or streaming (0) loads / stores
     // activations entering the layer: [P][B][ld_in]; or, with gather != null, rows X[gather[j][m]]
     const void* in; int ld_in; size_t in_stride;
     const int32_t* gather; long gather_stride;
