@@ -493,25 +493,30 @@ def test_split_storage_returns_every_fp32_pattern_exactly():
 
 
 # ----------------------------------------------------------------- random ragged shapes
-def test_random_ragged_shapes_mixed_precision():
-    """Forty seeded random models (1-3 layers, widths any multiple of 8 up to 312, class counts on both sides
-    of the head-kernel limit, batches from 1 to 130, 1-5 learners): two meta rounds each against the
-    oracle.  Covers tile tails in every dimension of every kernel, and the clamped loads behind them."""
-    torch = _torch()
+@pytest.mark.parametrize("bf16", [True, False], ids=["bf16", "fp32"])
+def test_random_ragged_shapes(bf16):
+    """Forty seeded random models (1-3 layers; widths any multiple of 8 up to 312 in mixed precision, any
+    width up to 199 in fp32; class counts on both sides of the head-kernel limit; batches from 1 to 130;
+    1-5 learners): two meta rounds each against the oracle.  Covers tile tails in every dimension of
+    every kernel, and the clamped loads behind them."""
+    _torch()
     rng = np.random.default_rng(123)
+    tol = TOL_BF16 if bf16 else TOL_FP32
+    dtype = kavg.KAVG_BF16 if bf16 else kavg.KAVG_FP32
     for case in range(40):
         L = int(rng.integers(1, 4))
-        dims = [int(rng.integers(1, 40)) * 8 for _ in range(L)] + [int(rng.choice([2, 3, 7, 10, 13, 16, 17, 24, 33]))]
+        widths = [int(rng.integers(1, 40)) * 8 if bf16 else int(rng.integers(1, 200)) for _ in range(L)]
+        dims = widths + [int(rng.choice([2, 3, 7, 10, 13, 16, 17, 24, 33]))]
         P, K = int(rng.integers(1, 6)), int(rng.integers(1, 4))
         B = int(rng.choice([1, 5, 16, 33, 64, 70, 130]))
-        data = synth.make_dataset(300, dims[0], dims[-1], bf16=True, seed_data=case, seed_teacher=case + 1,
+        data = synth.make_dataset(300, dims[0], dims[-1], bf16=bf16, seed_data=case, seed_teacher=case + 1,
                                   teacher_hidden=16)
         w0 = synth.he_normal_params(dims, case + 2)
-        g = kavg.MAvg(P, K, 0.05, 0.7, dims, B, kavg.KAVG_BF16, index_seed=case + 3)
-        X, y = _to_device(data, True)
+        g = kavg.MAvg(P, K, 0.05, 0.7, dims, B, dtype, index_seed=case + 3)
+        X, y = _to_device(data, bf16)
         g.set_data(X, y)
         g.set_params(w0)
-        o = O.MAvgOracle(P, K, 0.05, 0.7, dims, B, bf16=True, index_seed=case + 3)
+        o = O.MAvgOracle(P, K, 0.05, 0.7, dims, B, bf16=bf16, index_seed=case + 3)
         o.set_data(data["X32"], data["y"])
         o.set_params(w0)
         tag = "case %d dims %s P=%d K=%d B=%d" % (case, dims, P, K, B)
@@ -521,9 +526,9 @@ def test_random_ragged_shapes_mixed_precision():
             assert np.array_equal(g.indices(), o.indices()), tag
             for j in range(P):
                 e = worst_error(g.replica(j), o.replica(j), dims)
-                assert e < TOL_BF16, "%s: replica %d round %d: %.3g" % (tag, j, r, e)
+                assert e < tol, "%s: replica %d round %d: %.3g" % (tag, j, r, e)
             g.meta_update()
             o.meta_update()
             e = worst_error(g.params(), o.params(), dims)
-            assert e < TOL_BF16, "%s: global model round %d: %.3g" % (tag, r, e)
+            assert e < tol, "%s: global model round %d: %.3g" % (tag, r, e)
         g.close()
