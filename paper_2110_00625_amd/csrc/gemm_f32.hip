@@ -62,8 +62,9 @@ struct Args {
 // Where thread `tid` finds its NPER elements of a slice: element i is (x, k) with the memory-
 // contiguous index running fastest over the threads.
 struct Mover {
-    const float* p[NPER];   // address for k = 0 (null: x outside the operand); unused for k-gathered operands
+    const float* p[NPER];   // address for k = 0 of the (clamped) row x
     int x[NPER], k[NPER];
+    bool ok[NPER];          // x lies inside the operand
 };
 
 __device__ __forceinline__ void mover_init(Mover& m, const Operand& o, int learner, int x0, int nX, int tid) {
@@ -75,21 +76,36 @@ __device__ __forceinline__ void mover_init(Mover& m, const Operand& o, int learn
         const int e = tid + 256 * i;
         if (kfast) { m.x[i] = e / BK; m.k[i] = e % BK; } else { m.x[i] = e % TILE; m.k[i] = e / TILE; }
         const int x = x0 + m.x[i];
-        m.p[i] = nullptr;
-        if (x < nX) {
-            const long row = (g && !o.gather_on_k) ? (long)g[x] : (long)x;
-            m.p[i] = base + row * o.ld_x;
-        }
+        m.ok[i] = x < nX;
+        const int xc = m.ok[i] ? x : nX - 1;
+        const long row = (g && !o.gather_on_k) ? (long)g[xc] : (long)xc;
+        m.p[i] = base + row * o.ld_x;
     }
 }
 
-__device__ __forceinline__ float mover_load(const Mover& m, const Operand& o, int learner, int i, int k, int nK) {
-    if (!m.p[i] || k >= nK) return 0.f;
+// The thread's NPER elements of the slice starting at k0.  No load is predicated: positions outside
+// the operand or beyond k_end are read from clamped addresses and replaced by zeros, so that all
+// loads of the slice are in flight together; with a gather on the contraction index, all row
+// indices are requested first, then all elements (one wait, not one per element).
+__device__ __forceinline__ void mover_load_all(const Mover& m, const Operand& o, int learner, int k0, int k_end,
+                                               float (&out)[NPER]) {
+    long off[NPER];
     if (o.gather && o.gather_on_k) {
         const int32_t* g = o.gather + (long)learner * o.gather_stride;
-        return m.p[i][(long)g[k] * o.ld_k];
+        int32_t row[NPER];
+#pragma unroll
+        for (int i = 0; i < NPER; ++i) row[i] = g[min(k0 + m.k[i], k_end - 1)];
+#pragma unroll
+        for (int i = 0; i < NPER; ++i) off[i] = (long)row[i] * o.ld_k;
+    } else {
+#pragma unroll
+        for (int i = 0; i < NPER; ++i) off[i] = (long)min(k0 + m.k[i], k_end - 1) * o.ld_k;
     }
-    return m.p[i][(long)k * o.ld_k];
+    float v[NPER];
+#pragma unroll
+    for (int i = 0; i < NPER; ++i) v[i] = m.p[i][off[i]];
+#pragma unroll
+    for (int i = 0; i < NPER; ++i) out[i] = (m.ok[i] && k0 + m.k[i] < k_end) ? v[i] : 0.f;
 }
 
 template <int EPI>
@@ -110,11 +126,8 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(Args a) {
 
     float acc[4][4] = {};
     float rv_next[NPER], cv_next[NPER];
-#pragma unroll
-    for (int i = 0; i < NPER; ++i) {
-        rv_next[i] = mover_load(mr, a.R, learner, i, k_begin + mr.k[i], k_end);
-        cv_next[i] = mover_load(mc, a.C, learner, i, k_begin + mc.k[i], k_end);
-    }
+    mover_load_all(mr, a.R, learner, k_begin, k_end, rv_next);
+    mover_load_all(mc, a.C, learner, k_begin, k_end, cv_next);
     for (int k0 = k_begin; k0 < k_end; k0 += BK) {
 #pragma unroll
         for (int i = 0; i < NPER; ++i) {
@@ -123,11 +136,8 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(Args a) {
         }
         __syncthreads();
         if (k0 + BK < k_end) {
-#pragma unroll
-            for (int i = 0; i < NPER; ++i) {      // next slice in flight during the FMAs
-                rv_next[i] = mover_load(mr, a.R, learner, i, k0 + BK + mr.k[i], k_end);
-                cv_next[i] = mover_load(mc, a.C, learner, i, k0 + BK + mc.k[i], k_end);
-            }
+            mover_load_all(mr, a.R, learner, k0 + BK, k_end, rv_next);      // next slice in flight during the FMAs
+            mover_load_all(mc, a.C, learner, k0 + BK, k_end, cv_next);
         }
 #pragma unroll
         for (int k = 0; k < BK; ++k) {
@@ -173,8 +183,17 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(Args a) {
         const int r = r0 + tid;
         if (r < a.nR) {
             const float* dz = a.dz + (size_t)learner * a.dz_stride;
+            // eight rows requested together, added in ascending order
             float s = 0.f;
-            for (int m = 0; m < a.nK; ++m) s += dz[(size_t)m * a.ld_dz + r];
+            int m = 0;
+            for (; m + 8 <= a.nK; m += 8) {
+                float t[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) t[u] = dz[(size_t)(m + u) * a.ld_dz + r];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) s += t[u];
+            }
+            for (; m < a.nK; ++m) s += dz[(size_t)m * a.ld_dz + r];
             const size_t at = (size_t)learner * a.bias_stride + r;
             if (a.ub) { s = a.beta * a.ub[at] + s; a.ub[at] = s; }
             a.bias_rw[at] = a.bias_rw[at] - a.lr * s;
@@ -192,8 +211,18 @@ finish_forward_kernel(const float* __restrict__ partial, size_t split_stride, in
     const int c = (int)(e % ld_out);
     if (c >= nC) return;
     const int learner = (int)(e / per_learner);
+    // eight partials are requested together, then added in ascending order (same sum, one round trip
+    // to memory per eight splits instead of one per split)
     float z = 0.f;
-    for (int s = 0; s < splits; ++s) z += partial[(size_t)s * split_stride + e];
+    int s = 0;
+    for (; s + 8 <= splits; s += 8) {
+        float t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = partial[(size_t)(s + u) * split_stride + e];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) z += t[u];
+    }
+    for (; s < splits; ++s) z += partial[(size_t)s * split_stride + e];
     z += bias[(size_t)learner * bias_stride + c];
     if (relu) z = fmaxf(z, 0.f);
     out[e] = z;
