@@ -36,12 +36,11 @@ Readings where the paper is silent (each repeated in the design notes):
   own u across meta rounds (it is not reset when the learner restarts from
   w~), u = 0 initially.  beta = 0 is Algorithm 1 as printed.
 * mixed precision ("bf16" mode): the operands of every matrix product are
-  rounded to bf16 (nearest; ties to even, except the weights, whose ties go
-  away from zero -- the rounding that lets an fp32 master be kept exactly as
-  its bf16 value plus a 16-bit remainder): the weights as used in forward and
-  data-gradient products, the stored hidden activations, and the gradient
-  dZ_l that flows backward through layer l (used for the weight gradient, the
-  bias gradient and the data gradient alike).  Accumulation, logits, softmax,
+  rounded to bf16, nearest with ties to even (the IEEE default conversion):
+  the weights as used in forward and data-gradient products, the stored
+  hidden activations, and the gradient dZ_l that flows backward through
+  layer l (used for the weight gradient, the bias gradient and the data
+  gradient alike).  Accumulation, logits, softmax,
   loss, the SGD update of the master parameters and the whole meta step stay
   in full precision.  The data set itself is given on the bf16 grid.
 
@@ -101,15 +100,6 @@ def rne_bf16(x: np.ndarray) -> np.ndarray:
     the magnitudes that occur)."""
     m, e = np.frexp(np.asarray(x, dtype=np.float64))
     return np.ldexp(np.rint(m * 256.0) / 256.0, e)
-
-
-def rna_bf16(x: np.ndarray) -> np.ndarray:
-    """Nearest bf16 value of each float64, ties away from zero.  This is the
-    rounding of the *weights* in the mixed-precision reading: adding half a
-    unit to the magnitude and cutting the fp32 pattern to its top 16 bits.
-    It differs from rne_bf16 only on exact ties."""
-    m, e = np.frexp(np.asarray(x, dtype=np.float64))
-    return np.ldexp(np.sign(m) * np.floor(np.abs(m) * 256.0 + 0.5) / 256.0, e)
 
 
 def _identity(x):
@@ -181,9 +171,8 @@ def backward(Ws, Zs, As, dZL, q=_identity):
 def minibatch_gradient(w, dims, Xb, yb, bf16=False):
     """(mean loss, flat gradient) of the minibatch objective at w."""
     q = rne_bf16 if bf16 else _identity
-    qw = rna_bf16 if bf16 else _identity
     Ws, bs = unpack(w, dims)
-    Wq = [qw(W) for W in Ws]
+    Wq = [q(W) for W in Ws]
     Zs, As = forward(Wq, bs, Xb, q)
     loss, dZL = softmax_cross_entropy(Zs[-1], yb)
     gWs, gbs = backward(Wq, Zs, As, dZL, q)
@@ -252,30 +241,50 @@ class MAvgOracle:
         self.user_idx = None if idx is None else np.asarray(idx, dtype=np.int32).reshape(
             self.P, self.K, self.B)
 
-    def local_steps(self, learners=None):
-        """K minibatch-SGD steps on every learner (or only on the listed ones)."""
+    def _learner_steps(self, j):
+        """The K local steps of learner j on its own replica (Algorithm 1, inner loop).  Touches
+        nothing but replica j (and velocity j); returns its indices, losses and gradient sum."""
         N = self.X.shape[0]
+        idx = np.zeros((self.K, self.B), dtype=np.int32)
+        losses = np.zeros(self.K)
+        gsum = np.zeros(self.n)
+        w = self.reps[j]
+        for k in range(self.K):
+            if self.user_idx is not None:
+                ib = self.user_idx[j, k]
+            else:
+                ib = minibatch_indices(self.seed, j, self.t0 + k, self.B, N)
+            idx[k] = ib
+            Xb = self.X[ib].astype(np.float64)
+            yb = self.y[ib]
+            loss, g = minibatch_gradient(w, self.dims, Xb, yb, self.bf16)
+            losses[k] = loss
+            gsum += g
+            if self.beta > 0.0:
+                self.u[j] = self.beta * self.u[j] + g
+                w -= self.lr * self.u[j]
+            else:
+                w -= self.lr * g      # in place: w is a view of replica j
+        return idx, losses, gsum
+
+    def local_steps(self, learners=None, workers=1):
+        """K minibatch-SGD steps on every learner (or only on the listed ones).  The learners of
+        Algorithm 1 work independently between two meta steps ("in parallel"), so with workers > 1
+        they are walked by that many threads; nothing a learner computes depends on that."""
+        todo = list(range(self.P) if learners is None else learners)
+        if workers > 1 and len(todo) > 1:
+            from concurrent.futures import ThreadPoolExecutor
+            with ThreadPoolExecutor(max_workers=workers) as pool:
+                results = list(pool.map(self._learner_steps, todo))
+        else:
+            results = [self._learner_steps(j) for j in todo]
         idx = np.zeros((self.P, self.K, self.B), dtype=np.int32)
         losses = np.zeros((self.K, self.P))
         self.grad_sum = np.zeros(self.n)
-        for j in (range(self.P) if learners is None else learners):
-            w = self.reps[j]
-            for k in range(self.K):
-                if self.user_idx is not None:
-                    ib = self.user_idx[j, k]
-                else:
-                    ib = minibatch_indices(self.seed, j, self.t0 + k, self.B, N)
-                idx[j, k] = ib
-                Xb = self.X[ib].astype(np.float64)
-                yb = self.y[ib]
-                loss, g = minibatch_gradient(w, self.dims, Xb, yb, self.bf16)
-                losses[k, j] = loss
-                self.grad_sum += g
-                if self.beta > 0.0:
-                    self.u[j] = self.beta * self.u[j] + g
-                    w -= self.lr * self.u[j]
-                else:
-                    w -= self.lr * g      # in place: w is a view of replica j
+        for j, (idx_j, losses_j, gsum_j) in zip(todo, results):
+            idx[j] = idx_j
+            losses[:, j] = losses_j
+            self.grad_sum += gsum_j
         self.t0 += self.K
         self.last_idx, self.last_losses = idx, losses
 

@@ -4,6 +4,9 @@ before touching the device."""
 import ctypes
 import os
 import re
+import subprocess
+
+import numpy as np
 
 import pytest
 
@@ -83,3 +86,45 @@ def test_flat_meta_update_rejects_bad_arguments(lib):
 def test_null_context_is_an_error(lib):
     for name in ("kavg_local_steps", "kavg_meta_update", "kavg_destroy"):
         assert getattr(lib, name)(None) == kavg.KAVG_EINVAL
+
+
+def test_split_storage_contract_on_the_host(tmp_path):
+    """The library keeps a learner's fp32 parameter as two 16-bit planes (csrc/split.h).  Contract,
+    stated here and checked on the header's own functions compiled for the host:
+      hi   = top 16 bits of (pattern + 0x8000): the nearest bf16 value, exact ties away from zero;
+      lo   = low 16 bits of the pattern;
+      join(hi, lo) returns the pattern, whatever it is.
+    hi differs from the nearest-even conversion only on exact ties (lo == 0x8000 with an even kept
+    mantissa), where it is one bf16 unit further from zero."""
+    src = tmp_path / "shim.cpp"
+    src.write_text(
+        '#include "%s"\n'
+        'extern "C" void split_all(const unsigned* in, unsigned* hi, unsigned* lo, unsigned* back, long n) {\n'
+        '  for (long i = 0; i < n; ++i) { hi[i] = kavg::split_hi(in[i]); lo[i] = kavg::split_lo(in[i]);\n'
+        '                                 back[i] = kavg::split_join(hi[i], lo[i]); } }\n'
+        % os.path.join(ROOT, "paper_2110_00625_amd", "csrc", "split.h"))
+    so = tmp_path / "shim.so"
+    subprocess.run(["g++", "-O1", "-shared", "-fPIC", str(src), "-o", str(so)], check=True)
+    shim = ctypes.CDLL(str(so))
+    rng = np.random.default_rng(3)
+    bits = rng.integers(0, 1 << 32, size=400000, dtype=np.uint64).astype(np.uint32)
+    bits &= np.uint32(0xBFFFFFFF)                                  # finite values
+    keep = np.arange(0x3F00, 0x4100, dtype=np.uint32)
+    ties = (keep << np.uint32(16)) | np.uint32(0x8000)
+    near = np.concatenate([ties - 1, ties + 1, ties | np.uint32(0x80000000), keep << np.uint32(16),
+                           (keep << np.uint32(16)) | np.uint32(0xFFFF)])
+    bits = np.concatenate([bits, ties, near, np.array([0, 0x80000000, 0x00800000, 0x0000FFFF], dtype=np.uint32)])
+    hi, lo, back = (np.empty_like(bits) for _ in range(3))
+    vp = ctypes.c_void_p
+    shim.split_all.argtypes = [vp, vp, vp, vp, ctypes.c_long]
+    shim.split_all(bits.ctypes.data, hi.ctypes.data, lo.ctypes.data, back.ctypes.data, bits.size)
+    assert np.array_equal(back, bits)
+    assert np.array_equal(hi, ((bits.astype(np.uint64) + 0x8000) >> 16).astype(np.uint32) & np.uint32(0xFFFF))
+    assert np.array_equal(lo, bits & np.uint32(0xFFFF))
+    # against the nearest-even conversion (the oracle's): equal except on ties with an even kept mantissa
+    import torch
+    rne = torch.from_numpy(bits.view(np.float32).copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    differ = hi.astype(np.uint16) != rne
+    is_tie_even = ((bits & np.uint32(0xFFFF)) == 0x8000) & (((bits >> np.uint32(16)) & 1) == 0)
+    assert np.array_equal(differ, is_tie_even)
+    assert np.all(hi[differ].astype(np.int64) - rne[differ].astype(np.int64) == 1)

@@ -6,7 +6,7 @@ import pytest
 
 from oracle import mavg_oracle as O
 from paper_2110_00625_amd import kavg, synth
-from tests.util import flat_error, worst_error
+from tests.util import bf16_plane_bits, flat_error, worst_error
 
 pytestmark = pytest.mark.gpu
 
@@ -112,9 +112,8 @@ def test_meta_update_flat_matches_oracle(P, n, shadow):
         assert np.array_equal(rg[:, :n], np.tile(w.cpu().numpy(), (P, 1)))
         assert np.all(rg[:, n:] == 0)                                 # padding untouched
         if shadow:
-            # the bf16 copies are the weights' rounding of the oracle: nearest, ties away from zero
-            want = O.rna_bf16(w.cpu().numpy().astype(np.float64)).astype(np.float32)
-            want_bits = (want.view(np.uint32) >> 16).astype(np.uint16)
+            # the bf16 copies follow the library's documented storage rule (stated in tests/util.py)
+            want_bits = bf16_plane_bits(w.cpu().numpy())
             got_bits = sh.cpu().numpy().view(np.uint16)
             assert np.array_equal(got_bits[:, :n], np.tile(want_bits, (P, 1)))
 

@@ -367,3 +367,76 @@ def test_learner_momentum_zero_is_algorithm_1():
             o.local_steps()
             o.meta_update()
     assert np.array_equal(a.params(), b.params())
+
+
+# ------------------------------------------------------------------ resume (set_state)
+@pytest.mark.parametrize("bf16", [False, True], ids=["fp64", "bf16"])
+def test_set_state_resumes_the_run_where_it_stopped(bf16):
+    """Global model, momentum buffer and round counter are the whole state of Algorithm 1 between
+    rounds (every learner restarts from the global model): a run cut after round 2 and resumed from
+    those three continues exactly like the uninterrupted one, including the minibatches it draws
+    (learner j's step counter is round * K)."""
+    P, K, B, lr, mu = 3, 2, 4, 0.1, 0.8
+    X, y, w0 = _problem(DIMS, 120, 21)
+    a = O.MAvgOracle(P, K, lr, mu, DIMS, B, bf16=bf16, index_seed=5)
+    a.set_params(w0)
+    a.set_data(X, y)
+    for _ in range(2):
+        a.local_steps()
+        a.meta_update()
+    w, v, r = a.params(), a.momentum(), a.round
+    assert r == 2
+    b = O.MAvgOracle(P, K, lr, mu, DIMS, B, bf16=bf16, index_seed=5)
+    b.set_data(X, y)
+    b.set_state(w, v, r)
+    for j in range(P):
+        assert np.array_equal(b.replica(j), w)                 # learners restart from the global model
+    for _ in range(2):
+        a.local_steps()
+        a.meta_update()
+        b.local_steps()
+        b.meta_update()
+        assert np.array_equal(a.indices(), b.indices())
+        assert np.array_equal(a.params(), b.params()) and np.array_equal(a.momentum(), b.momentum())
+        assert np.array_equal(a.losses(), b.losses())
+    assert b.round == 4
+    # the resumed run's draws are those of steps round*K .. : not the first steps' again
+    for j in range(P):
+        for k in range(K):
+            assert np.array_equal(b.indices()[j, k], O.minibatch_indices(5, j, 3 * K + k, B, 120))
+    assert not np.array_equal(b.indices()[0, 0], O.minibatch_indices(5, 0, 0, B, 120))
+
+
+def test_set_state_at_round_zero_with_zero_momentum_is_set_params():
+    X, y, w0 = _problem(DIMS, 80, 22)
+    a = O.MAvgOracle(2, 2, 0.1, 0.9, DIMS, 3, index_seed=9)
+    a.set_params(w0)
+    b = O.MAvgOracle(2, 2, 0.1, 0.9, DIMS, 3, index_seed=9)
+    b.set_state(w0, np.zeros_like(w0), 0)
+    for o in (a, b):
+        o.set_data(X, y)
+        o.local_steps()
+        o.meta_update()
+    assert np.array_equal(a.params(), b.params()) and np.array_equal(a.momentum(), b.momentum())
+    # a momentum buffer handed in is used: the next global model moves by mu * v more
+    c = O.MAvgOracle(2, 2, 0.1, 0.9, DIMS, 3, index_seed=9)
+    c.set_state(w0, np.full_like(w0, 0.01), 0)
+    c.set_data(X, y)
+    c.local_steps()
+    c.meta_update()
+    assert np.allclose(c.params() - a.params(), 0.9 * 0.01, rtol=0, atol=1e-12)
+
+
+def test_learners_walked_by_threads_give_the_same_run():
+    X, y, w0 = _problem(DIMS, 150, 23)
+    runs = []
+    for workers in (1, 3):
+        o = O.MAvgOracle(5, 3, 0.1, 0.9, DIMS, 4, index_seed=3)
+        o.set_params(w0)
+        o.set_data(X, y)
+        for _ in range(2):
+            o.local_steps(workers=workers)
+            o.meta_update()
+        runs.append((o.params(), o.momentum(), o.losses(), o.indices(), o.grad_sum))
+    for a, b in zip(*runs):
+        assert np.array_equal(a, b)

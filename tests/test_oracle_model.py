@@ -180,3 +180,41 @@ def test_bf16_mode_rounding_points_against_library_casts():
     _, g_exact = O.minibatch_gradient(w, dims, X, y, bf16=False)
     assert np.max(np.abs(g - g_exact)) < 2e-2 * np.max(np.abs(g_exact))
     assert np.max(np.abs(g - g_exact)) > 0.0
+
+
+def test_bf16_mode_rounds_weight_ties_to_even():
+    """Weights that sit exactly between two bf16 values (constructed: low half of the fp32 pattern =
+    0x8000, odd and even kept mantissas, both signs) enter the products rounded to the even
+    neighbour: the gradient agrees with a derivation that uses the library's cast for the weights
+    and differs from one that sends the ties away from zero."""
+    dims, B = (8, 6, 4), 5
+    rng = np.random.default_rng(13)
+    n = O.num_params(dims)
+    keep = rng.integers(0x3E00, 0x3F80, size=n).astype(np.uint32)            # magnitudes 0.125 .. 1
+    sign = rng.integers(0, 2, size=n).astype(np.uint32) << np.uint32(31)
+    w32 = (((keep << np.uint32(16)) | np.uint32(0x8000)) | sign).view(np.float32)
+    w = w32.astype(np.float64)
+    X = _bf(torch.tensor(rng.standard_normal((B, dims[0])))).numpy()
+    y = rng.integers(0, dims[-1], size=B)
+    _, g = O.minibatch_gradient(w, dims, X, y, bf16=True)
+
+    def derive(round_w):
+        Ws, bs = O.unpack(w, dims)
+        W1, W2 = round_w(torch.tensor(Ws[0])), round_w(torch.tensor(Ws[1]))
+        z1 = torch.tensor(X) @ W1.T + torch.tensor(bs[0])
+        a1 = _bf(torch.relu(z1))
+        z2 = a1 @ W2.T + torch.tensor(bs[1])
+        oh = torch.nn.functional.one_hot(torch.tensor(y), dims[-1]).to(torch.float64)
+        dz2 = _bf((torch.softmax(z2, dim=1) - oh) / B)
+        dz1 = _bf((dz2 @ W2) * (z1 > 0))
+        return torch.cat([(dz1.T @ torch.tensor(X)).reshape(-1), dz1.sum(0),
+                          (dz2.T @ a1).reshape(-1), dz2.sum(0)]).numpy()
+
+    def away(t):                                   # add half a unit to the magnitude, cut to 16 bits
+        bits = t.to(torch.float32).numpy().view(np.uint32).astype(np.uint64)
+        return torch.tensor((((bits + 0x8000) >> 16) << 16).astype(np.uint32).view(np.float32).astype(np.float64))
+
+    want = derive(_bf)
+    assert np.max(np.abs(g - want)) < 1e-15 + 1e-13 * np.max(np.abs(want))
+    other = derive(away)
+    assert np.max(np.abs(g - other)) > 1e-4 * np.max(np.abs(want))            # the tie rule is visible here

@@ -22,22 +22,34 @@ def tensor_errors(got, want, dims):
     return errs
 
 
-def worst_error(got, want, dims):
-    """Largest per-tensor error over the weight matrices and over bias vectors that have moved
-    away from zero (a bias tensor that is still ~0 has no scale to be relative to: it is
-    measured against the scale of its layer's weights instead)."""
+def worst_error(got, want, dims, verbose=False):
+    """Largest per-tensor relative error, every W_l and b_l measured against its own largest
+    magnitude in the oracle.  A bias tensor that is still numerically zero (max |b| < 1e-6: biases
+    start at 0) has no scale of its own and is measured against its layer's weights instead."""
     worst = 0.0
     sl = dict(layer_slices(dims))
     for l in range(1, len(dims)):
         w = np.asarray(want[sl["W%d" % l]], dtype=np.float64)
         g = np.asarray(got[sl["W%d" % l]], dtype=np.float64)
         wscale = float(np.max(np.abs(w)))
-        worst = max(worst, float(np.max(np.abs(g - w))) / max(wscale, 1e-30))
+        ew = float(np.max(np.abs(g - w))) / max(wscale, 1e-30)
         b = np.asarray(want[sl["b%d" % l]], dtype=np.float64)
         gb = np.asarray(got[sl["b%d" % l]], dtype=np.float64)
-        bscale = max(float(np.max(np.abs(b))), wscale)
-        worst = max(worst, float(np.max(np.abs(gb - b))) / max(bscale, 1e-30))
+        bscale = float(np.max(np.abs(b)))
+        if bscale < 1e-6:
+            bscale = wscale
+        eb = float(np.max(np.abs(gb - b))) / max(bscale, 1e-30)
+        if verbose:
+            print("    W%d %.3g  b%d %.3g" % (l, ew, l, eb))
+        worst = max(worst, ew, eb)
     return worst
+
+
+def bf16_plane_bits(x32):
+    """The 16-bit patterns the library documents for its bf16 copies of fp32 values (include/kavg.h):
+    nearest bf16, exact ties away from zero, i.e. the top half of (pattern + 0x8000)."""
+    bits = np.ascontiguousarray(x32, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return (((bits + 0x8000) >> 16) & 0xFFFF).astype(np.uint16)
 
 
 def flat_error(got, want):
