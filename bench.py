@@ -80,7 +80,7 @@ def source_digest():
     return h.hexdigest()[:16]
 
 
-def stored_traffic(kernel_class):
+def stored_traffic(workload, kernel_class):
     """HBM bytes per launch from the rocprofv3 --pmc runs recorded under profiles/,
     or None when absent or taken from other kernel sources than the current ones."""
     path = os.path.join(ROOT, "profiles", "pmc_traffic.json.txt")
@@ -92,15 +92,19 @@ def stored_traffic(kernel_class):
         return None
     if rec.get("source_digest") != source_digest():
         return None
-    return rec.get("traffic_bytes_per_launch", {}).get(kernel_class)
+    return rec.get("traffic_bytes_per_launch", {}).get(workload, {}).get(kernel_class)
 
 
-def cpu_baseline(w, data, learners, rounds, beta=0.0):
-    """The oracle, as it stands, on `rounds` meta rounds of this workload restricted to its first
-    `learners` learners (learners are independent between meta steps, so the rate per
-    learner-sample is that of the full workload)."""
+def cpu_baseline(w, data, beta=0.0, target_flops=1.0e12):
+    """The oracle, as it stands, on whole meta rounds of this workload restricted to its first
+    learners (learners are independent between meta steps, so the rate per learner-sample is that
+    of the full workload).  The sample is sized to about target_flops of arithmetic (some tens of
+    seconds on the host), never less than one learner for one round."""
     from threadpoolctl import threadpool_info
     from oracle import mavg_oracle as O
+    per_learner_round = w.K * flops_per_learner_step(w.dims, w.B)
+    learners = max(1, min(w.P, int(target_flops / per_learner_round)))
+    rounds = max(1, min(3, int(target_flops / (learners * per_learner_round))))
     o = O.MAvgOracle(learners, w.K, w.lr, w.mu, w.dims, w.B, bf16=(w.dtype == kavg.KAVG_BF16),
                      index_seed=w.seeds["index"], learner_momentum=beta)
     o.set_data(data["X32"], data["y"])
@@ -112,8 +116,10 @@ def cpu_baseline(w, data, learners, rounds, beta=0.0):
     dt = time.perf_counter() - t0
     threads = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
     return {"value": rounds * learners * w.K * w.B / dt, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
-            "sample": "%d meta rounds of the same workload with %d of its %d learners (%.1f s of CPU time)" % (
-                rounds, learners, w.P, dt)}
+            "threads": "BLAS threads of numpy's matmul (the rest of the oracle is single-threaded numpy)",
+            "host_cores_available": len(os.sched_getaffinity(0)),
+            "sample": "%d meta round(s) of %s with %d of its %d learners: %d learner-samples, %.1f s of wall time" % (
+                rounds, w.name, learners, w.P, rounds * learners * w.K * w.B, dt)}
 
 
 def bench_meta_only(torch, passes=200, warmup=5):
@@ -154,16 +160,150 @@ def bench_meta_only(torch, passes=200, warmup=5):
             "frac": gbs / HBM_PEAK_GBS}
 
 
+def bench_ceilings(torch, nbytes=1 << 31, reps=10):
+    """What this device reaches with the meta step's access pattern and nothing else to do
+    (kavg_probe): read-only, write-only and 1:1 read/write streams over `nbytes`, and a chain of
+    bf16 matrix-core instructions without memory traffic."""
+    a = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").normal_()
+    b = torch.empty_like(a)
+    sink = torch.zeros(1, device="cuda")
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    out = {"bytes": nbytes, "pattern": "16-byte non-temporal accesses, 16 interleaved rows per lane"}
+    for name, kind in (("read_GBps", kavg.PROBE_READ), ("write_GBps", kavg.PROBE_WRITE), ("copy_GBps", kavg.PROBE_COPY)):
+        for _ in range(2):
+            kavg.kavg_probe(kind, a, b, sink=sink)
+        ev0.record()
+        work = 0.0
+        for _ in range(reps):
+            work += kavg.kavg_probe(kind, a, b, sink=sink)
+        ev1.record()
+        torch.cuda.synchronize()
+        out[name] = work / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    kavg.kavg_probe(kavg.PROBE_MFMA, iters=2000, sink=sink)
+    ev0.record()
+    work = kavg.kavg_probe(kavg.PROBE_MFMA, iters=20000, sink=sink)
+    ev1.record()
+    torch.cuda.synchronize()
+    out["mfma_bf16_TFLOPs"] = work / (ev0.elapsed_time(ev1) * 1e-3) / 1e12
+    return out
+
+
+def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration=False):
+    """`warmup` untimed meta rounds (every kernel class bracketed by HIP events: the per-class
+    breakdown), then `steps` timed ones with inputs resident in device memory.  Returns the
+    measurements and the host-side inputs (for the CPU baseline)."""
+    data = synth.make_workload_inputs(w)
+    bf = w.dtype == kavg.KAVG_BF16
+    g = kavg.MAvg(w.P, w.K, w.lr, w.mu, w.dims, w.B, w.dtype, index_seed=w.seeds["index"])
+    X = torch.from_numpy(data["Xbits"].view(np.int16) if bf else data["X32"]).cuda()
+    y = torch.from_numpy(data["y"]).cuda()
+    g.set_data(X, y)
+    if learner_momentum > 0:
+        g.set_learner_momentum(learner_momentum)
+    g.set_params(data["w0"])
+
+    if copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                  # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        del src, dst
+
+    classes = ["index", "forward", "loss", "backward", "update", "meta", "head"]
+    g.profile(classes)
+    for _ in range(max(warmup, 1)):
+        g.local_steps()
+        g.meta_update()
+    breakdown = g.profile_read()
+    heavy = max(("forward", "backward", "update", "meta"), key=lambda c: breakdown[c][0])
+
+    # timed region: only the dominant class carries events, and only one launch in EVERY of it
+    # (an event pair costs ~10 us of stream time; 17 is coprime with the launches per round, so
+    # the sample walks evenly over the layers)
+    EVERY = 17
+    g.profile([heavy], every=EVERY)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        g.local_steps()
+        g.meta_update()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = g.profile_read()
+    g.profile([])
+    loss_last = float(g.losses()[-1].mean())
+    g.close()
+    del X, y
+    torch.cuda.empty_cache()
+
+    samples = w.P * w.K * w.B * steps
+    by, fl = class_model(w, learner_momentum > 0)
+    ms_sampled, sampled = prof[heavy]
+    per_round = w.K if heavy != "meta" else 1
+    n_layers = len(w.dims) - 1
+    head = w.dims[-1] <= 16
+    per_step = {"meta": 1, "update": n_layers - (1 if head else 0), "forward": n_layers - (1 if head else 0),
+                "backward": n_layers - 1 - (1 if head else 0)}[heavy]
+    launches = per_step * per_round * steps
+    ms_heavy = ms_sampled / max(sampled, 1) * launches         # sampled mean launch time x all launches of the class
+    bytes_heavy = by[heavy] * per_round * steps                # all launches of the class in the timed region
+    flops_heavy = fl[heavy] * per_round * steps
+    t_hbm = bytes_heavy / (HBM_PEAK_GBS * 1e9)
+    peak_flops = (MFMA_BF16_PEAK_TFLOPS if bf else FP32_PEAK_TFLOPS) * 1e12
+    t_mfma = flops_heavy / peak_flops
+    if t_hbm >= t_mfma or heavy == "meta":
+        achieved = bytes_heavy / (ms_heavy * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS}
+    else:
+        achieved = flops_heavy / (ms_heavy * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": peak_flops / 1e12, "unit": "TFLOP/s",
+                "frac": achieved / (peak_flops / 1e12)}
+    roof.update({"traffic": stored_traffic(w.name, heavy), "kernel_class": heavy, "launches": launches,
+                 "launches_timed": sampled, "avg_launch_us": 1e3 * ms_heavy / max(launches, 1),
+                 "algorithmic_bytes_per_launch": bytes_heavy / max(launches, 1),
+                 "flops_per_launch": flops_heavy / max(launches, 1)})
+
+    # all dense products of the local steps against the matrix-core peak (context for the roofline)
+    gemm_ms = sum(breakdown[c][0] for c in ("forward", "backward", "update"))
+    gemm_flops = sum(fl[c] for c in ("forward", "backward", "update")) * w.K * max(warmup, 1)
+    local_mfma = {"achieved_TFLOPs": gemm_flops / (gemm_ms * 1e-3) / 1e12, "peak_TFLOPs": peak_flops / 1e12,
+                  "frac": gemm_flops / (gemm_ms * 1e-3) / peak_flops,
+                  "note": "forward+backward+update launches of the profiled warm-up rounds"}
+    # every class against the HBM roofline, from the bracketed warm-up rounds
+    per_class = {}
+    for c in classes:
+        ms_c = breakdown[c][0] / max(warmup, 1)
+        if c in by and ms_c > 0:
+            rounds_bytes = by[c] * (1 if c == "meta" else w.K)
+            per_class[c] = {"ms_per_round": ms_c, "hbm_frac": rounds_bytes / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        else:
+            per_class[c] = {"ms_per_round": ms_c}
+    res = {
+        "value": samples / dt, "ms_per_step": 1e3 * dt / steps, "steps": steps, "warmup": warmup,
+        "dtype": "bf16" if bf else "f32",
+        "config": {"workload": "%s: P=%d K=%d B=%d mu=%g lr=%g MLP %s, N=%d%s" % (
+            w.name, w.P, w.K, w.B, w.mu, w.lr, "-".join(map(str, w.dims)), w.N,
+            ", learner momentum %g" % learner_momentum if learner_momentum > 0 else ""),
+            "step": "one meta round = K local steps on P learners + fused meta step",
+            "samples_per_step": w.P * w.K * w.B, "flops_per_step": flops_per_learner_step(w.dims, w.B) * w.P * w.K},
+        "roofline": roof, "local_steps_mfma": local_mfma, "kernel_classes": per_class, "final_mean_loss": loss_last,
+    }
+    return res, data
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cifar_mlp", choices=[k for k, v in WORKLOADS.items() if v.dims])
+    ap.add_argument("--workload", default="large", choices=[k for k, v in WORKLOADS.items() if v.dims],
+                    help="the headline workload (default: the largest single-GPU configuration)")
+    ap.add_argument("--also", default="noisy_wide,cifar_mlp,tiny",
+                    help="comma-separated further workloads reported under other_workloads ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-meta-only", action="store_true")
-    ap.add_argument("--cpu-learners", type=int, default=16)
-    ap.add_argument("--cpu-rounds", type=int, default=3)
+    ap.add_argument("--no-ceilings", action="store_true")
     ap.add_argument("--learner-momentum", type=float, default=0.0,
                     help="heavy-ball momentum inside every learner (variant of Section 2; default off = Algorithm 1)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -180,107 +320,29 @@ def main():
         sys.exit(1)
     kavg.load_library()
     w = WORKLOADS[args.workload]
-    data = synth.make_workload_inputs(w)
-    bf = w.dtype == kavg.KAVG_BF16
-
-    g = kavg.MAvg(w.P, w.K, w.lr, w.mu, w.dims, w.B, w.dtype, index_seed=w.seeds["index"])
-    X = torch.from_numpy(data["Xbits"].view(np.int16) if bf else data["X32"]).cuda()
-    y = torch.from_numpy(data["y"]).cuda()
-    g.set_data(X, y)
-    if args.learner_momentum > 0:
-        g.set_learner_momentum(args.learner_momentum)
-    g.set_params(data["w0"])
-
-    if args.copy_calibration:
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        dst.copy_(src)                                  # 1 GiB read + 1 GiB written
-        torch.cuda.synchronize()
-        del src, dst
-
-    # warm-up rounds, every kernel class bracketed: gives the per-class breakdown
-    classes = ["index", "forward", "loss", "backward", "update", "meta", "head"]
-    g.profile(classes)
-    for _ in range(max(args.warmup, 1)):
-        g.local_steps()
-        g.meta_update()
-    breakdown = g.profile_read()
-    heavy = max(("forward", "backward", "update", "meta"), key=lambda c: breakdown[c][0])
-
-    # timed region: only the dominant class carries events, and only one launch in EVERY of it
-    # (an event pair costs ~10 us of stream time; 17 is coprime with the launches per round, so
-    # the sample walks evenly over the layers)
-    EVERY = 17
-    g.profile([heavy], every=EVERY)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        g.local_steps()
-        g.meta_update()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    prof = g.profile_read()
-    g.profile([])
-    loss_last = float(g.losses()[-1].mean())
-
-    samples = w.P * w.K * w.B * args.steps
-    by, fl = class_model(w, args.learner_momentum > 0)
-    ms_sampled, sampled = prof[heavy]
-    per_round = w.K if heavy != "meta" else 1
-    n_layers = len(w.dims) - 1
-    head = w.dims[-1] <= 16
-    per_step = {"meta": 1, "update": n_layers - (1 if head else 0), "forward": n_layers - (1 if head else 0),
-                "backward": n_layers - 1 - (1 if head else 0)}[heavy]
-    launches = per_step * per_round * args.steps
-    ms_heavy = ms_sampled / max(sampled, 1) * launches         # sampled mean launch time x all launches of the class
-    bytes_heavy = by[heavy] * per_round * args.steps           # all launches of the class in the timed region
-    flops_heavy = fl[heavy] * per_round * args.steps
-    t_hbm = bytes_heavy / (HBM_PEAK_GBS * 1e9)
-    peak_flops = (MFMA_BF16_PEAK_TFLOPS if bf else FP32_PEAK_TFLOPS) * 1e12
-    t_mfma = flops_heavy / peak_flops
-    traffic = stored_traffic(heavy)
-    if t_hbm >= t_mfma or heavy == "meta":
-        achieved = bytes_heavy / (ms_heavy * 1e-3) / 1e9
-        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS}
-    else:
-        achieved = flops_heavy / (ms_heavy * 1e-3) / 1e12
-        roof = {"bound": "mfma", "achieved": achieved, "peak": peak_flops / 1e12, "unit": "TFLOP/s",
-                "frac": achieved / (peak_flops / 1e12)}
-    roof.update({"traffic": traffic, "kernel_class": heavy, "launches": launches, "launches_timed": sampled,
-                 "avg_launch_us": 1e3 * ms_heavy / max(launches, 1),
-                 "algorithmic_bytes_per_launch": bytes_heavy / max(launches, 1),
-                 "flops_per_launch": flops_heavy / max(launches, 1)})
-
-    # all dense products of the local steps against the matrix-core peak (context for the roofline)
-    gemm_ms = sum(breakdown[c][0] for c in ("forward", "backward", "update"))
-    gemm_flops = sum(fl[c] for c in ("forward", "backward", "update")) * w.K * max(args.warmup, 1)
-    local_mfma = {"achieved_TFLOPs": gemm_flops / (gemm_ms * 1e-3) / 1e12, "peak_TFLOPs": peak_flops / 1e12,
-                  "frac": gemm_flops / (gemm_ms * 1e-3) / peak_flops,
-                  "note": "forward+backward+update launches of the profiled warm-up rounds"}
-
+    res, data = run_workload(torch, w, args.steps, args.warmup, args.learner_momentum, args.copy_calibration)
     out = {
         "metric": "learner-samples/sec (all P on 1 GPU); meta-update GB/s vs HBM peak",
-        "value": samples / dt, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16" if bf else "f32", "data": "synthetic",
-        "config": {"workload": "%s: P=%d K=%d B=%d mu=%g lr=%g MLP %s, N=%d%s" % (
-            w.name, w.P, w.K, w.B, w.mu, w.lr, "-".join(map(str, w.dims)), w.N,
-            ", learner momentum %g" % args.learner_momentum if args.learner_momentum > 0 else ""),
-            "step": "one meta round = K local steps on P learners + fused meta step",
-            "samples_per_step": w.P * w.K * w.B, "flops_per_step": flops_per_learner_step(w.dims, w.B) * w.P * w.K},
-        "roofline": roof,
-        "local_steps_mfma": local_mfma,
-        "kernel_ms_per_round": {c: breakdown[c][0] / max(args.warmup, 1) for c in classes},
-        "final_mean_loss": loss_last,
+        "value": res["value"], "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": res["dtype"], "data": "synthetic", "config": res["config"],
+        "roofline": res["roofline"], "local_steps_mfma": res["local_steps_mfma"],
+        "kernel_classes": res["kernel_classes"], "final_mean_loss": res["final_mean_loss"],
     }
-    if not args.no_meta_only:
-        g.close()
-        del X, y
-        torch.cuda.empty_cache()
-        out["meta_update"] = bench_meta_only(torch)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, data, min(args.cpu_learners, w.P), args.cpu_rounds, args.learner_momentum)
+        out["cpu_baseline"] = cpu_baseline(w, data, args.learner_momentum)
+    del data
+    others = {}
+    for name in [x for x in args.also.split(",") if x and x != args.workload]:
+        r, _ = run_workload(torch, WORKLOADS[name], min(args.steps, 20), min(args.warmup, 3))
+        others[name] = {k: r[k] for k in ("value", "ms_per_step", "steps", "dtype", "config", "roofline",
+                                          "local_steps_mfma", "kernel_classes")}
+    if others:
+        out["other_workloads"] = others
+    if not args.no_meta_only:
+        out["meta_update"] = bench_meta_only(torch)
+    if not args.no_ceilings:
+        out["ceilings"] = bench_ceilings(torch)
     print(json.dumps(out))
 
 

@@ -185,6 +185,25 @@ int kavg_profile_read(kavg_ctx* ctx, double* ms_out, long long* launches_out);
  * thread-unsafe HIP call may be made on this thread's behalf on that stream. */
 int kavg_graph(kavg_ctx* ctx, int on);
 
+/* Measurement aid (not part of the method): one launch of a probe kernel on hip_stream, so that a
+ * benchmark can state what this device reaches with the access pattern of the fused meta step of
+ * Algorithm 1 (every lane owns a 16-byte piece of each of 16 interleaved rows, non-temporal):
+ *   KAVG_PROBE_READ   reads `bytes` of a_dev;         KAVG_PROBE_WRITE  overwrites `bytes` of a_dev;
+ *   KAVG_PROBE_COPY   reads a_dev, writes b_dev (equal parts, like the meta step);
+ *   KAVG_PROBE_MFMA   `iters` x 4 independent v_mfma_f32_32x32x16_bf16 per wavefront, 8 workgroups
+ *                     per compute unit, no memory traffic (buffers unused).
+ * a_dev / b_dev: device blocks of at least `bytes` (16-byte aligned; rounded down to a multiple of
+ * 256 bytes), sink_dev: one float of device memory (never written in practice).  *work_out (host)
+ * receives the bytes moved (both directions counted) or the flops of the launch.  Asynchronous;
+ * the caller times it.  Errors: KAVG_EINVAL (unknown kind, null / misaligned pointers, bytes < 256,
+ * iters < 1), KAVG_EDEVICE. */
+#define KAVG_PROBE_READ  0
+#define KAVG_PROBE_WRITE 1
+#define KAVG_PROBE_COPY  2
+#define KAVG_PROBE_MFMA  3
+int kavg_probe(int kind, void* a_dev, void* b_dev, size_t bytes, int iters, float* sink_dev,
+               void* hip_stream, double* work_out);
+
 uint64_t    kavg_round(const kavg_ctx* ctx);
 const char* kavg_last_error(const kavg_ctx* ctx);   /* ctx == NULL: text of the last failed kavg_init */
 int         kavg_destroy(kavg_ctx* ctx);            /* waits for the stream, frees the host context  */

@@ -90,6 +90,13 @@ char g_init_error[256] = "";
 
 }  // namespace
 
+// No exception may cross the C boundary: host allocations inside the library (layout tables, event
+// pools, staging vectors) are the only possible source.
+#define KAVG_NOTHROW_BEGIN try {
+#define KAVG_NOTHROW_END(ctx)                                                                   \
+    } catch (const std::bad_alloc&) { return fail(ctx, KAVG_ENOMEM, "host allocation failed"); } \
+    catch (...) { return fail(ctx, KAVG_ENOMEM, "unexpected host failure"); }
+
 struct kavg_ctx {
     int P, K, B, L, dtype;
     float lr, mu;
@@ -270,7 +277,7 @@ size_t kavg_num_params(int n_layers, const int* dims) {
 
 size_t kavg_workspace_bytes(int P, int K, int B, int n_layers, const int* dims, int dtype) {
     if (!shapes_ok(P, K, B, n_layers, dims, dtype)) return 0;
-    return make_layout(P, K, B, n_layers, dims, dtype).total;
+    try { return make_layout(P, K, B, n_layers, dims, dtype).total; } catch (...) { return 0; }
 }
 
 int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, const int* dims, int B,
@@ -278,6 +285,8 @@ int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, co
               void* hip_stream) {
     if (!out) return fail(nullptr, KAVG_EINVAL, "out is null");
     *out = nullptr;
+    kavg_ctx* c = nullptr;
+    try {
     if (!shapes_ok(P, K, B, n_layers, dims, dtype))
         return fail(nullptr, KAVG_EINVAL, "bad shape: need P,K,B >= 1 (P,K <= 2^24, B <= 65536), "
                     "dims >= 1 and, for bf16, d_0..d_{L-1} multiples of 8");
@@ -288,7 +297,7 @@ int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, co
     Layout lo = make_layout(P, K, B, n_layers, dims, dtype);
     if (workspace_bytes < lo.total)
         return fail(nullptr, KAVG_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, lo.total);
-    kavg_ctx* c = new (std::nothrow) kavg_ctx();
+    c = new (std::nothrow) kavg_ctx();
     if (!c) return fail(nullptr, KAVG_ENOMEM, "host allocation failed");
     c->P = P; c->K = K; c->B = B; c->L = n_layers; c->dtype = dtype;
     c->lr = lr; c->mu = mu; c->seed = index_seed;
@@ -312,6 +321,10 @@ int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, co
     }
     *out = c;
     return KAVG_OK;
+    } catch (...) {
+        delete c;
+        return fail(nullptr, KAVG_ENOMEM, "host allocation failed");
+    }
 }
 
 int kavg_set_params(kavg_ctx* c, const float* w0_host) {
@@ -421,6 +434,7 @@ int kavg_local_steps(kavg_ctx* c) {
     if ((uint64_t)c->t0 + (uint64_t)c->K > ((uint64_t)1 << 24))
         return fail(c, KAVG_ESTATE, "local step counter would exceed 2^24");
     hipStream_t st = c->stream;
+    KAVG_NOTHROW_BEGIN
     {
         Bracket br(c, KAVG_CLASS_INDEX);
         if (c->user_idx)
@@ -452,11 +466,13 @@ int kavg_local_steps(kavg_ctx* c) {
     c->t0 += (uint32_t)c->K;
     c->have_steps = true;
     return KAVG_OK;
+    KAVG_NOTHROW_END(c)
 }
 
 int kavg_meta_update(kavg_ctx* c) {
     if (!c) return KAVG_EINVAL;
     if (!c->have_params) return fail(c, KAVG_ESTATE, "no parameters: call kavg_set_params first");
+    KAVG_NOTHROW_BEGIN
     {
         Bracket br(c, KAVG_CLASS_META);
         if (c->dtype == KAVG_BF16)
@@ -469,6 +485,7 @@ int kavg_meta_update(kavg_ctx* c) {
     }
     c->round += 1;
     return KAVG_OK;
+    KAVG_NOTHROW_END(c)
 }
 
 static int copy_out(kavg_ctx* c, const void* src, void* dst_host, size_t bytes) {
@@ -497,6 +514,7 @@ int kavg_replica(kavg_ctx* c, int j, float* out_host, size_t n) {
     if (!c->have_params) return fail(c, KAVG_ESTATE, "no parameters yet");
     if (c->dtype != KAVG_BF16) return copy_out(c, c->reps() + (size_t)j * c->lo.stride, out_host, n * 4);
     // bf16 mode: fetch the learner's two planes and join them into fp32 values on the host
+    KAVG_NOTHROW_BEGIN
     std::vector<uint16_t> hi(n), lo(n);
     int rc = copy_out(c, c->hi_planes() + (size_t)j * c->lo.stride, hi.data(), n * 2);
     if (rc == KAVG_OK) rc = copy_out(c, c->lo_planes() + (size_t)j * c->lo.stride, lo.data(), n * 2);
@@ -506,6 +524,7 @@ int kavg_replica(kavg_ctx* c, int j, float* out_host, size_t n) {
         memcpy(out_host + e, &bits, 4);
     }
     return KAVG_OK;
+    KAVG_NOTHROW_END(c)
 }
 
 int kavg_losses(kavg_ctx* c, float* out_host) {
@@ -620,6 +639,19 @@ int kavg_meta_update_flat(float* w_tilde_dev, float* v_dev, float* replicas_dev,
     if (shadow_dev && shadow_stride < n) return KAVG_EINVAL;
     hipError_t e = launch_meta_update(w_tilde_dev, v_dev, replicas_dev, replica_stride, shadow_dev,
                                       shadow_stride, P, n, mu, shadows_stay_cached(P, n), (hipStream_t)hip_stream);
+    return e == hipSuccess ? KAVG_OK : KAVG_EDEVICE;
+}
+
+int kavg_probe(int kind, void* a_dev, void* b_dev, size_t bytes, int iters, float* sink_dev, void* hip_stream,
+               double* work_out) {
+    if (kind < KAVG_PROBE_READ || kind > KAVG_PROBE_MFMA || !sink_dev || !work_out) return KAVG_EINVAL;
+    if (kind == KAVG_PROBE_MFMA) {
+        if (iters < 1) return KAVG_EINVAL;
+    } else {
+        if (!a_dev || ((uintptr_t)a_dev & 15) || bytes < 256) return KAVG_EINVAL;
+        if (kind == KAVG_PROBE_COPY && (!b_dev || ((uintptr_t)b_dev & 15))) return KAVG_EINVAL;
+    }
+    const hipError_t e = launch_probe(kind, a_dev, b_dev, bytes, iters, sink_dev, (hipStream_t)hip_stream, work_out);
     return e == hipSuccess ? KAVG_OK : KAVG_EDEVICE;
 }
 

@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "../../include/kavg.h"
+
 namespace kavg {
 
 // ---- minibatch index stream (Algorithm 1: "randomly sample a mini-batch") ----
@@ -91,5 +93,10 @@ bool head_supported(int C);
 hipError_t head_forward_backward(const LayerCall& c, const int32_t* y, const int32_t* idx, long idx_lstride,
                                  float* rowloss, int bf16, hipStream_t st);
 hipError_t head_update(const LayerCall& c, const int32_t* idx, long idx_lstride, int bf16, hipStream_t st);
+
+// ---- device ceilings (measurement aid) ----
+// one launch of the probe `kind` (KAVG_PROBE_*); *work_out = bytes moved or flops done by it
+hipError_t launch_probe(int kind, void* a, void* b, size_t bytes, int iters, float* sink, hipStream_t st,
+                        double* work_out);
 
 }  // namespace kavg

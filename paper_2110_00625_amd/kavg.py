@@ -20,7 +20,7 @@ EXPORTS = [
     "kavg_set_data", "kavg_set_indices", "kavg_local_steps", "kavg_meta_update", "kavg_params",
     "kavg_momentum", "kavg_replica", "kavg_losses", "kavg_indices", "kavg_round", "kavg_last_error",
     "kavg_destroy", "kavg_meta_update_flat", "kavg_profile", "kavg_profile_read",
-    "kavg_velocity_bytes", "kavg_set_learner_momentum", "kavg_velocity", "kavg_graph",
+    "kavg_velocity_bytes", "kavg_set_learner_momentum", "kavg_velocity", "kavg_graph", "kavg_probe",
 ]
 CLASS_NAMES = ["index", "forward", "loss", "backward", "update", "meta", "head"]
 
@@ -75,6 +75,7 @@ def load_library():
         "kavg_profile_read": [c_vp, c_vp, c_vp],
         "kavg_graph": [c_vp, c_int],
         "kavg_meta_update_flat": [c_vp, c_vp, c_vp, c_sz, c_vp, c_sz, c_int, c_sz, c_f, c_vp],
+        "kavg_probe": [c_int, c_vp, c_vp, c_sz, c_int, c_vp, c_vp, ctypes.POINTER(ctypes.c_double)],
     }.items():
         fn = getattr(lib, name)
         fn.restype = c_int
@@ -121,6 +122,23 @@ def kavg_meta_update_flat(w_tilde, v, replicas, mu, shadow=None, stream=None):
                         else "HIP launch failed")
 
 
+PROBE_READ, PROBE_WRITE, PROBE_COPY, PROBE_MFMA = 0, 1, 2, 3
+
+
+def kavg_probe(kind, a=None, b=None, iters=1, sink=None, stream=None):
+    """One probe launch on the current stream; returns the bytes moved / flops done by it."""
+    import torch
+    lib = load_library()
+    st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    work = ctypes.c_double(0.0)
+    nbytes = 0 if a is None else a.numel() * a.element_size()
+    rc = lib.kavg_probe(int(kind), None if a is None else a.data_ptr(), None if b is None else b.data_ptr(),
+                        nbytes, int(iters), sink.data_ptr(), st, ctypes.byref(work))
+    if rc != KAVG_OK:
+        raise KavgError(rc, "kavg_probe rejected its arguments" if rc == KAVG_EINVAL else "HIP launch failed")
+    return work.value
+
+
 class MAvg:
     """One kavg_ctx plus the torch tensors it borrows (workspace, data set, indices)."""
 
@@ -135,8 +153,8 @@ class MAvg:
         if nbytes == 0:
             raise KavgError(KAVG_EINVAL, "kavg_workspace_bytes rejected the configuration")
         torch.cuda.set_device(self.device)
-        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         self.stream = torch.cuda.current_stream(self.device)
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         rc = self.lib.kavg_init(ctypes.byref(self.ctx), P, K, float(lr), float(mu), len(self.dims) - 1,
                                 _dims_array(self.dims), B, dtype, int(index_seed),
                                 self.workspace.data_ptr(), nbytes, self.stream.cuda_stream)
