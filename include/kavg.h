@@ -90,6 +90,24 @@ int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu,
               int n_layers, const int* dims, int B, int dtype, uint64_t index_seed,
               void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
+/* kavg_init for callers that cannot allocate device memory (code running under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the context works in a block of
+ * KAVG_STATIC_WORKSPACE_BYTES that lives inside the library's device image (one copy per GPU, held
+ * until the process ends) instead of a caller workspace.  Neither this call nor any later call on
+ * the context allocates or frees device memory.  Everything else is kavg_init: same arguments,
+ * same kernels, same results; data set, index array and velocity block are still the caller's.
+ * The block keeps whatever the previous context left in it; every piece a context reads is
+ * written by it first (the range flag is cleared here, the rest by kavg_set_params / the kernels).
+ * One context per device may use the block at a time: a second kavg_init_static on the same
+ * device before kavg_destroy of the first returns KAVG_ESTATE (two contexts would race on it).
+ * Errors: as kavg_init, plus KAVG_ENOMEM when kavg_workspace_bytes(...) exceeds
+ * KAVG_STATIC_WORKSPACE_BYTES (checked before any device call), KAVG_EDEVICE when the block's
+ * address cannot be obtained. */
+#define KAVG_STATIC_WORKSPACE_BYTES ((size_t)32 << 20)
+int kavg_init_static(kavg_ctx** out, int P, int K, float lr, float mu,
+                     int n_layers, const int* dims, int B, int dtype, uint64_t index_seed,
+                     void* hip_stream);
+
 /* "initialize w~_1; v <- 0" of Algorithm 1, and "set w^j = w~_1": copies n
  * floats from w0_host into the global model, zeroes the momentum buffer,
  * writes every replica, resets round and step counters. */

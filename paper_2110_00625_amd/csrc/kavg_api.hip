@@ -88,7 +88,18 @@ Layout make_layout(int P, int K, int B, int L, const int* dims, int dtype) {
 
 char g_init_error[256] = "";
 
+// ---- workspace inside the library, for callers that cannot allocate device memory ----
+// One block per device (every GPU that loads the library holds its own copy until the process
+// ends).  In host code the array's name is only a handle: its device address is looked up once per
+// device with hipGetSymbolAddress and kept in g_static_ptr; everything below uses that pointer.
+constexpr size_t STATIC_WS_BYTES = KAVG_STATIC_WORKSPACE_BYTES;
+constexpr int MAX_DEVICES = 64;
+void* g_static_ptr[MAX_DEVICES] = {};          // device address of `scratch` on device d (null: not looked up yet)
+kavg_ctx* g_static_owner[MAX_DEVICES] = {};    // the context that currently works in it
+
 }  // namespace
+
+static __device__ __align__(256) unsigned char scratch[KAVG_STATIC_WORKSPACE_BYTES];
 
 // No exception may cross the C boundary: host allocations inside the library (layout tables, event
 // pools, staging vectors) are the only possible source.
@@ -127,6 +138,7 @@ struct kavg_ctx {
     bool graph_on = false;
     bool warm = false;                  // the sequence has run eagerly once with the current pointers
     hipGraphExec_t gexec = nullptr;
+    int static_dev = -1;                // >= 0: the context works in the library's own workspace of that device
 
     float* w_tilde() const { return (float*)(ws + lo.off_w); }
     float* v() const { return (float*)(ws + lo.off_v); }
@@ -325,6 +337,38 @@ int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, co
         delete c;
         return fail(nullptr, KAVG_ENOMEM, "host allocation failed");
     }
+}
+
+int kavg_init_static(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, const int* dims, int B,
+                     int dtype, uint64_t index_seed, void* hip_stream) {
+    if (!out) return fail(nullptr, KAVG_EINVAL, "out is null");
+    *out = nullptr;
+    const size_t need = kavg_workspace_bytes(P, K, B, n_layers, dims, dtype);
+    if (need == 0)
+        return fail(nullptr, KAVG_EINVAL, "bad shape: need P,K,B >= 1 (P,K <= 2^24, B <= 65536), "
+                    "dims >= 1 and, for bf16, d_0..d_{L-1} multiples of 8");
+    if (need > STATIC_WS_BYTES)
+        return fail(nullptr, KAVG_ENOMEM, "this configuration needs %zu bytes of workspace, the library's own block "
+                    "holds %zu: use kavg_init with a caller workspace", need, STATIC_WS_BYTES);
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(nullptr, KAVG_EDEVICE, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(nullptr, KAVG_EINVAL, "device ordinal %d not supported", dev);
+    if (!g_static_ptr[dev]) {               // once per device, with that device current
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(nullptr, KAVG_EDEVICE, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        g_static_ptr[dev] = ptr;
+    }
+    if (g_static_owner[dev])
+        return fail(nullptr, KAVG_ESTATE, "the library's workspace on device %d is in use by another context", dev);
+    const int rc = kavg_init(out, P, K, lr, mu, n_layers, dims, B, dtype, index_seed, g_static_ptr[dev],
+                             STATIC_WS_BYTES, hip_stream);
+    if (rc != KAVG_OK) return rc;
+    (*out)->static_dev = dev;
+    g_static_owner[dev] = *out;
+    return KAVG_OK;
 }
 
 int kavg_set_params(kavg_ctx* c, const float* w0_host) {
@@ -624,6 +668,7 @@ const char* kavg_last_error(const kavg_ctx* c) { return c ? c->err : g_init_erro
 int kavg_destroy(kavg_ctx* c) {
     if (!c) return KAVG_EINVAL;
     hipError_t e = hipStreamSynchronize(c->stream);
+    if (c->static_dev >= 0 && g_static_owner[c->static_dev] == c) g_static_owner[c->static_dev] = nullptr;
     if (c->gexec) (void)hipGraphExecDestroy(c->gexec);
     for (int k = 0; k < KAVG_NCLASS; ++k)
         for (hipEvent_t ev : c->prof_ev[k]) (void)hipEventDestroy(ev);

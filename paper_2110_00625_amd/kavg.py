@@ -20,8 +20,9 @@ EXPORTS = [
     "kavg_set_data", "kavg_set_indices", "kavg_local_steps", "kavg_meta_update", "kavg_params",
     "kavg_momentum", "kavg_replica", "kavg_losses", "kavg_indices", "kavg_round", "kavg_last_error",
     "kavg_destroy", "kavg_meta_update_flat", "kavg_profile", "kavg_profile_read",
-    "kavg_velocity_bytes", "kavg_set_learner_momentum", "kavg_velocity", "kavg_graph", "kavg_probe",
+    "kavg_velocity_bytes", "kavg_set_learner_momentum", "kavg_velocity", "kavg_graph", "kavg_init_static", "kavg_probe",
 ]
+STATIC_WORKSPACE_BYTES = 32 << 20
 CLASS_NAMES = ["index", "forward", "loss", "backward", "update", "meta", "head"]
 
 
@@ -56,6 +57,9 @@ def load_library():
     lib.kavg_init.restype = c_int
     lib.kavg_init.argtypes = [ctypes.POINTER(c_vp), c_int, c_int, c_f, c_f, c_int, ip, c_int, c_int,
                               ctypes.c_uint64, c_vp, c_sz, c_vp]
+    lib.kavg_init_static.restype = c_int
+    lib.kavg_init_static.argtypes = [ctypes.POINTER(c_vp), c_int, c_int, c_f, c_f, c_int, ip, c_int, c_int,
+                                     ctypes.c_uint64, c_vp]
     for name, args in {
         "kavg_set_params": [c_vp, c_vp],
         "kavg_set_state": [c_vp, c_vp, c_vp, ctypes.c_uint64],
@@ -142,7 +146,10 @@ def kavg_probe(kind, a=None, b=None, iters=1, sink=None, stream=None):
 class MAvg:
     """One kavg_ctx plus the torch tensors it borrows (workspace, data set, indices)."""
 
-    def __init__(self, P, K, lr, mu, dims, B, dtype=KAVG_FP32, index_seed=0, device="cuda:0"):
+    def __init__(self, P, K, lr, mu, dims, B, dtype=KAVG_FP32, index_seed=0, device="cuda:0",
+                 static_workspace=False):
+        """static_workspace: work in the library's own device block (kavg_init_static) instead of a
+        torch allocation."""
         import torch
         self._torch = torch
         self.lib = load_library()
@@ -154,10 +161,16 @@ class MAvg:
             raise KavgError(KAVG_EINVAL, "kavg_workspace_bytes rejected the configuration")
         torch.cuda.set_device(self.device)
         self.stream = torch.cuda.current_stream(self.device)
-        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
-        rc = self.lib.kavg_init(ctypes.byref(self.ctx), P, K, float(lr), float(mu), len(self.dims) - 1,
-                                _dims_array(self.dims), B, dtype, int(index_seed),
-                                self.workspace.data_ptr(), nbytes, self.stream.cuda_stream)
+        if static_workspace:
+            self.workspace = None
+            rc = self.lib.kavg_init_static(ctypes.byref(self.ctx), P, K, float(lr), float(mu), len(self.dims) - 1,
+                                           _dims_array(self.dims), B, dtype, int(index_seed),
+                                           self.stream.cuda_stream)
+        else:
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            rc = self.lib.kavg_init(ctypes.byref(self.ctx), P, K, float(lr), float(mu), len(self.dims) - 1,
+                                    _dims_array(self.dims), B, dtype, int(index_seed),
+                                    self.workspace.data_ptr(), nbytes, self.stream.cuda_stream)
         if rc != KAVG_OK:
             raise KavgError(rc, self.lib.kavg_last_error(None).decode())
         self.n = kavg_num_params(self.dims)

@@ -128,3 +128,19 @@ def test_split_storage_contract_on_the_host(tmp_path):
     is_tie_even = ((bits & np.uint32(0xFFFF)) == 0x8000) & (((bits >> np.uint32(16)) & 1) == 0)
     assert np.array_equal(differ, is_tie_even)
     assert np.all(hi[differ].astype(np.int64) - rne[differ].astype(np.int64) == 1)
+
+
+def test_static_workspace_init_rejects_oversize_before_any_device_call(lib):
+    """kavg_init_static sizes the configuration against the library's own block first: a
+    configuration that does not fit is refused with KAVG_ENOMEM (no device needed to say so),
+    a bad shape with KAVG_EINVAL."""
+    ctx = ctypes.c_void_p()
+    big = (3072, 1024, 1024, 10)
+    assert kavg.kavg_workspace_bytes(16, 8, 128, big, 1) > kavg.STATIC_WORKSPACE_BYTES
+    rc = lib.kavg_init_static(ctypes.byref(ctx), 16, 8, 0.1, 0.9, 3, kavg._dims_array(big), 128, 1, 0, None)
+    assert rc == kavg.KAVG_ENOMEM and not ctx.value
+    assert b"kavg_init" in lib.kavg_last_error(None)
+    rc = lib.kavg_init_static(ctypes.byref(ctx), 0, 8, 0.1, 0.9, 3, kavg._dims_array(big), 128, 1, 0, None)
+    assert rc == kavg.KAVG_EINVAL and not ctx.value
+    text = open(os.path.join(ROOT, "include", "kavg.h")).read()
+    assert "#define KAVG_STATIC_WORKSPACE_BYTES ((size_t)32 << 20)" in text and kavg.STATIC_WORKSPACE_BYTES == 32 << 20
