@@ -234,34 +234,40 @@ template <int X, int BK, int NT>
 struct DmaLoader {
     static constexpr int N = X * BK / 8 / NT;
     static constexpr int CPR = BK / 8;           // chunks per row
-    const uint16_t* row[N];      // start of the (clamped) memory row of piece i
-    int chunk[N];                // memory chunk (of 8 bf16) within the slice
+    const uint16_t* row[N];      // start of the (clamped) memory row of piece i, plus the piece's chunk offset
+    int chunk8[N];               // first element of the piece's memory chunk within a slice
+    int wave;                    // wavefront index, uniform (kept in a scalar register)
     __device__ __forceinline__ void init(const Operand& o, const uint16_t* base, const int32_t* gather, int x0, int tid) {
-        const int lane = tid & 63, wave = tid >> 6;
+        const int lane = tid & 63;
+        wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             const int slot = (wave * N + i) * 64 + lane;
             const int xr = slot / CPR;
             const int x = min(x0 + xr, o.n_rows - 1);
-            chunk[i] = (slot % CPR) ^ dma_swizzle<BK>(xr);
-            row[i] = base + (gather ? (long)gather[x] : (long)x) * o.ld;
+            chunk8[i] = ((slot % CPR) ^ dma_swizzle<BK>(xr)) * 8;
+            row[i] = base + (gather ? (long)gather[x] : (long)x) * o.ld + chunk8[i];
         }
     }
-    __device__ __forceinline__ void load(const Operand& o, int k0, uint16_t* tile, int tid) const {
+    // FULL: the slice lies inside the contraction (k0 + BK <= n_cont), no clamping needed
+    template <bool FULL>
+    __device__ __forceinline__ void load(const Operand& o, int k0, uint16_t* tile) const {
         typedef __attribute__((address_space(3))) void* lds_p;
         typedef const __attribute__((address_space(1))) void* glb_p;
-        const int wave = tid >> 6;
 #pragma unroll
         for (int i = 0; i < N; ++i) {
-            const int k = min(k0 + chunk[i] * 8, o.n_cont - 8);
+            const int k = FULL ? k0 : min(k0 + chunk8[i], o.n_cont - 8) - chunk8[i];
             __builtin_amdgcn_global_load_lds((glb_p)(row[i] + k), (lds_p)(tile + (wave * N + i) * 64 * 8), 16, 0, 0);
         }
     }
+    __device__ __forceinline__ void load(const Operand& o, int k0, uint16_t* tile, int) const {
+        if (k0 + BK <= o.n_cont) load<true>(o, k0, tile); else load<false>(o, k0, tile);
+    }
     __device__ __forceinline__ void fix_tail(const Operand& o, int k0, uint16_t* tile, int tid) const {
-        const int lane = tid & 63, wave = tid >> 6;
+        const int lane = tid & 63;
 #pragma unroll
         for (int i = 0; i < N; ++i)
-            if (k0 + chunk[i] * 8 >= o.n_cont) {
+            if (k0 + chunk8[i] >= o.n_cont) {
                 const u32x4 zero = {0u, 0u, 0u, 0u};
                 *(u32x4*)(tile + ((wave * N + i) * 64 + lane) * 8) = zero;
             }
@@ -281,8 +287,9 @@ struct Shape {
     static constexpr int MR = TR / (32 * WR), MC = TC / (32 * WC);
     static constexpr int WTC = MC * 32;                 // columns of a wavefront's tile
     static constexpr int SPITCH = WTC + 4;              // update epilogue: fp32 staging row, padded
-    static constexpr int R_ELEMS = PIPE == PIPE_DMA ? TR * BK : RTRANS ? BK * tpitch(TR) : TR * dpitch(BK);
-    static constexpr int C_ELEMS = PIPE == PIPE_DMA ? TC * BK : CTRANS ? BK * tpitch(TC) : TC * dpitch(BK);
+    static constexpr bool DIRECT = PIPE == PIPE_DMA;       // global -> LDS loads, unpadded swizzled tiles
+    static constexpr int R_ELEMS = DIRECT ? TR * BK : RTRANS ? BK * tpitch(TR) : TR * dpitch(BK);
+    static constexpr int C_ELEMS = DIRECT ? TC * BK : CTRANS ? BK * tpitch(TC) : TC * dpitch(BK);
     static constexpr int OPER_BYTES = (PIPE == PIPE_PLAIN ? 1 : 2) * (R_ELEMS + C_ELEMS) * 2;
     static constexpr int STAGE_BYTES = MODE == MODE_UPD ? 4 * 32 * SPITCH * 4 : 0;
     static constexpr int KRED_BYTES = WK > 1 ? WR * WC * MR * MC * 16 * 64 * 4 : 0;   // one k group's partial tiles
@@ -304,6 +311,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
     static_assert(MR >= 1 && MC >= 1, "tile too small for the wave grid");
     static_assert((BK / 16) % WK == 0, "slice must split evenly over the k groups");
     static_assert(MODE != MODE_UPD || (WK == 1 && NW == 4 && PIPE == PIPE_PLAIN), "the update epilogue assumes 4 wavefronts, no k split, one LDS buffer");
+    constexpr bool DIRECT = PIPE == PIPE_DMA;
     static_assert(NT % (TR / 8) == 0 && NT % (TC / 8) == 0, "loader column mapping");
     typedef Shape<MODE, TR, TC, WR, WC, WK, BK, RTRANS, CTRANS, PIPE> SH;
     constexpr int WTC = SH::WTC, SPITCH = SH::SPITCH, R_ELEMS = SH::R_ELEMS, C_ELEMS = SH::C_ELEMS;
@@ -356,30 +364,48 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
         if (RTRANS) rtl.store(rg, Rs + buf * BUF_ELEMS, tid); else rdl.store(rg, Rs + buf * BUF_ELEMS, tid);
         if (CTRANS) ctl.store(cg, Cs + buf * BUF_ELEMS, tid); else cdl.store(cg, Cs + buf * BUF_ELEMS, tid);
     };
-    auto multiply = [&](int buf) {
-        const uint16_t* R = Rs + buf * BUF_ELEMS;
-        const uint16_t* C = Cs + buf * BUF_ELEMS;
-#pragma unroll
-        for (int kq = 0; kq < BK / 16 / WK; ++kq) {
-            const int kk = wk * (BK / 16 / WK) + kq;
-            bf16x8 cf[MC], rf[MR];
+    // Fragments of k slab kq+1 are requested before the MFMAs of slab kq are issued (two register
+    // sets, statically indexed), so that the matrix cores do not wait for an LDS round trip per slab.
+    // Fragments of k slab kq+1 are requested before the MFMAs of slab kq are issued (two register
+    // sets, statically indexed), so that the matrix cores do not wait for an LDS round trip per slab.
+    auto multiply_tiles = [&](const uint16_t* R, const uint16_t* C) {
+        constexpr int KQ = BK / 16 / WK;
+        bf16x8 cf[2][MC], rf[2][MR];
+        auto fetch_frags = [&](int set, int kq) {
+            const int kk = wk * KQ + kq;
 #pragma unroll
             for (int j = 0; j < MC; ++j)
-                if constexpr (PIPE == PIPE_DMA) cf[j] = frag_swizzled<BK>(C, (wc * MC + j) * 32, kk, lane);
-                else cf[j] = CTRANS ? frag_trans<TC>(C, (wc * MC + j) * 32, kk, lane)
-                                    : frag_direct<BK>(C, (wc * MC + j) * 32, kk, lane);
+                if constexpr (DIRECT) cf[set][j] = frag_swizzled<BK>(C, (wc * MC + j) * 32, kk, lane);
+                else cf[set][j] = CTRANS ? frag_trans<TC>(C, (wc * MC + j) * 32, kk, lane)
+                                         : frag_direct<BK>(C, (wc * MC + j) * 32, kk, lane);
 #pragma unroll
             for (int i = 0; i < MR; ++i)
-                if constexpr (PIPE == PIPE_DMA) rf[i] = frag_swizzled<BK>(R, (wr * MR + i) * 32, kk, lane);
-                else rf[i] = RTRANS ? frag_trans<TR>(R, (wr * MR + i) * 32, kk, lane)
-                                    : frag_direct<BK>(R, (wr * MR + i) * 32, kk, lane);
+                if constexpr (DIRECT) rf[set][i] = frag_swizzled<BK>(R, (wr * MR + i) * 32, kk, lane);
+                else rf[set][i] = RTRANS ? frag_trans<TR>(R, (wr * MR + i) * 32, kk, lane)
+                                         : frag_direct<BK>(R, (wr * MR + i) * 32, kk, lane);
+        };
+        fetch_frags(0, 0);
+#pragma unroll
+        for (int kq = 0; kq < KQ; ++kq) {
+            if (kq + 1 < KQ) fetch_frags((kq + 1) & 1, kq + 1);
 #pragma unroll
             for (int i = 0; i < MR; ++i)
 #pragma unroll
                 for (int j = 0; j < MC; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf[j], rf[i], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf[kq & 1][j], rf[kq & 1][i], acc[i][j], 0, 0, 0);
+        }
+        // Pin that order for the instruction scheduler (it would otherwise fold the two fragment sets
+        // back into one and read each slab right before its MFMAs): LDS reads of slab 0, then for every
+        // slab the reads of the next one followed by its own MFMAs.
+        constexpr int DS_PER_SLAB = MC * ((!DIRECT && CTRANS) ? 2 : 1) + MR * ((!DIRECT && RTRANS) ? 2 : 1);
+        __builtin_amdgcn_sched_group_barrier(0x100, DS_PER_SLAB, 0);
+#pragma unroll
+        for (int kq = 0; kq < KQ; ++kq) {
+            if (kq + 1 < KQ) __builtin_amdgcn_sched_group_barrier(0x100, DS_PER_SLAB, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, MR * MC, 0);
         }
     };
+    auto multiply = [&](int buf) { multiply_tiles(Rs + buf * BUF_ELEMS, Cs + buf * BUF_ELEMS); };
 
     // Update epilogue: a lane owns eight consecutive columns of a row, 16 bytes of either plane.
     constexpr int L8_PER_ROW = WTC / 8;
@@ -767,10 +793,17 @@ hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     a.next_gather = c.gather ? c.next_gather : nullptr;
     // Tile shapes from measured sweeps (whole rounds, same box): wavefront tiles of 32x64 in both regimes
     // (128-byte row segments per plane), as 128x64 where the bf16 planes stay in the memory-side
-    // cache (CIFAR-MLP) and as 64x128 where they stream (the 4096-wide workloads).
+    // cache (CIFAR-MLP) and as 64x128 where they stream (the 4096-wide workloads with batches up to 128).
     if (c.shadow_cached) {
         if (c.gather) return launch<MODE_UPD, 128, 64, 4, 1, 1, 64, true, true, PIPE_PLAIN, true, true>(a, c.P, st);
         return launch<MODE_UPD, 128, 64, 4, 1, 1, 64, true, true, PIPE_PLAIN, true, false>(a, c.P, st);
+    }
+    if (c.B > 128) {
+        // Long contractions: per output tile the two operands (read out of the L2 cache, B rows each) weigh as
+        // much as the master tile itself, and a compute unit can only pull so many bytes per clock; a
+        // 128x128 tile reads a third less of them per weight (large: 15.0 -> 14.5 ms per round).
+        if (c.gather) return launch<MODE_UPD, 128, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, true>(a, c.P, st);
+        return launch<MODE_UPD, 128, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, false>(a, c.P, st);
     }
     if (c.gather) return launch<MODE_UPD, 64, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, true>(a, c.P, st);
     return launch<MODE_UPD, 64, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, false>(a, c.P, st);

@@ -272,10 +272,11 @@ def test_large_leaves_the_oracle_no_faster_than_a_cpu_fp32_twin(monkeypatch):
 
 
 # Launch shapes that only large problems select (128x128 and 64x128 forward / backward-data tiles,
-# the 128x64 backward-data tile, the streaming 64x128 update), on extents that are multiples of
-# none of them: widths 3080 / 4104, batches 70, 60 and 200, 24 classes.
-@pytest.mark.parametrize("P,B,sample", [(32, 70, (0, 31)), (16, 60, (3, 15)), (4, 200, (0, 3))],
-                         ids=["tiles128x128", "tiles64x128", "bwd128x64"])
+# the 128x64 backward-data tile, the streaming 64x128 update and the 128x128 update of batches
+# above 128), on extents that are multiples of none of them: widths 3080 / 4104, batches 70, 60
+# and 200, 24 classes.
+@pytest.mark.parametrize("P,B,sample", [(32, 70, (0, 31)), (16, 60, (3, 15)), (4, 200, (0, 3)), (8, 200, (0, 7))],
+                         ids=["tiles128x128", "tiles64x128", "bwd128x64", "update128x128"])
 def test_large_tile_shapes_on_ragged_extents(P, B, sample):
     torch = _torch()
     dims, N, lr = (3080, 4104, 4104, 24), 1500, 0.05
