@@ -188,7 +188,7 @@ def bench_ceilings(torch, nbytes=1 << 31, reps=10):
     return out
 
 
-def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration=False):
+def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration=False, refresh=1):
     """`warmup` untimed meta rounds (every kernel class bracketed by HIP events: the per-class
     breakdown), then `steps` timed ones with inputs resident in device memory.  Returns the
     measurements and the host-side inputs (for the CPU baseline)."""
@@ -201,6 +201,8 @@ def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration
     if learner_momentum > 0:
         g.set_learner_momentum(learner_momentum)
     g.set_params(data["w0"])
+    if refresh > 1:
+        g.set_refresh(min(refresh, w.K))
 
     if copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -209,7 +211,7 @@ def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration
         torch.cuda.synchronize()
         del src, dst
 
-    classes = ["index", "forward", "loss", "backward", "update", "meta", "head"]
+    classes = ["index", "forward", "loss", "backward", "update", "meta", "head", "correction"]
     g.profile(classes)
     for _ in range(max(warmup, 1)):
         g.local_steps()
@@ -259,7 +261,7 @@ def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration
         achieved = flops_heavy / (ms_heavy * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": peak_flops / 1e12, "unit": "TFLOP/s",
                 "frac": achieved / (peak_flops / 1e12)}
-    roof.update({"traffic": stored_traffic(w.name, heavy), "kernel_class": heavy, "launches": launches,
+    roof.update({"traffic": stored_traffic(w.name, heavy) if refresh == 1 else None, "kernel_class": heavy, "launches": launches,
                  "launches_timed": sampled, "avg_launch_us": 1e3 * ms_heavy / max(launches, 1),
                  "algorithmic_bytes_per_launch": bytes_heavy / max(launches, 1),
                  "flops_per_launch": flops_heavy / max(launches, 1)})
@@ -274,7 +276,7 @@ def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration
     per_class = {}
     for c in classes:
         ms_c = breakdown[c][0] / max(warmup, 1)
-        if c in by and ms_c > 0:
+        if c in by and ms_c > 0 and (refresh == 1 or c == "meta"):
             rounds_bytes = by[c] * (1 if c == "meta" else w.K)
             per_class[c] = {"ms_per_round": ms_c, "hbm_frac": rounds_bytes / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBS}
         else:
@@ -282,9 +284,10 @@ def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration
     res = {
         "value": samples / dt, "ms_per_step": 1e3 * dt / steps, "steps": steps, "warmup": warmup,
         "dtype": "bf16" if bf else "f32",
-        "config": {"workload": "%s: P=%d K=%d B=%d mu=%g lr=%g MLP %s, N=%d%s" % (
+        "config": {"workload": "%s: P=%d K=%d B=%d mu=%g lr=%g MLP %s, N=%d%s%s" % (
             w.name, w.P, w.K, w.B, w.mu, w.lr, "-".join(map(str, w.dims)), w.N,
-            ", learner momentum %g" % learner_momentum if learner_momentum > 0 else ""),
+            ", learner momentum %g" % learner_momentum if learner_momentum > 0 else "",
+            ", replicas refreshed every %d local steps (deferred updates)" % min(refresh, w.K) if refresh > 1 else ""),
             "step": "one meta round = K local steps on P learners + fused meta step",
             "samples_per_step": w.P * w.K * w.B, "flops_per_step": flops_per_learner_step(w.dims, w.B) * w.P * w.K},
         "roofline": roof, "local_steps_mfma": local_mfma, "kernel_classes": per_class, "final_mean_loss": loss_last,
@@ -301,6 +304,11 @@ def main():
                     help="the headline workload (default: the largest single-GPU configuration)")
     ap.add_argument("--also", default="noisy_wide,cifar_mlp,tiny",
                     help="comma-separated further workloads reported under other_workloads ('' = none)")
+    ap.add_argument("--refresh", type=int, default=1,
+                    help="headline workload: bring the stored replicas up to date every m local steps (deferred "
+                         "updates; 1 = every step, the default)")
+    ap.add_argument("--also-deferred", default="noisy_wide:16",
+                    help="workload:m pairs also run with deferred updates and reported under other_workloads ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-meta-only", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true")
@@ -320,7 +328,8 @@ def main():
         sys.exit(1)
     kavg.load_library()
     w = WORKLOADS[args.workload]
-    res, data = run_workload(torch, w, args.steps, args.warmup, args.learner_momentum, args.copy_calibration)
+    res, data = run_workload(torch, w, args.steps, args.warmup, args.learner_momentum, args.copy_calibration,
+                             refresh=args.refresh)
     out = {
         "metric": "learner-samples/sec (all P on 1 GPU); meta-update GB/s vs HBM peak",
         "value": res["value"], "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -337,6 +346,15 @@ def main():
         r, _ = run_workload(torch, WORKLOADS[name], min(args.steps, 20), min(args.warmup, 3))
         others[name] = {k: r[k] for k in ("value", "ms_per_step", "steps", "dtype", "config", "roofline",
                                           "local_steps_mfma", "kernel_classes")}
+    for pair in [x for x in args.also_deferred.split(",") if x]:
+        name, m = pair.split(":")
+        r, _ = run_workload(torch, WORKLOADS[name], min(args.steps, 20), min(args.warmup, 3), refresh=int(m))
+        # deferred updates change which bytes and flops a class moves; only times are reported for it
+        others["%s, replicas refreshed every %s steps" % (name, m)] = {
+            "value": r["value"], "ms_per_step": r["ms_per_step"], "steps": r["steps"], "dtype": r["dtype"],
+            "config": r["config"],
+            "flops_fraction_of_bf16_mfma_peak": r["config"]["flops_per_step"] / (r["ms_per_step"] * 1e-3) / (MFMA_BF16_PEAK_TFLOPS * 1e12),
+            "kernel_classes": {k: {"ms_per_round": v["ms_per_round"]} for k, v in r["kernel_classes"].items()}}
     if others:
         out["other_workloads"] = others
     if not args.no_meta_only:

@@ -169,6 +169,24 @@ size_t kavg_velocity_bytes(const kavg_ctx* ctx);
 int kavg_set_learner_momentum(kavg_ctx* ctx, float beta, void* velocity_dev, size_t bytes);
 int kavg_velocity(kavg_ctx* ctx, int j, float* out_host, size_t n);   /* u^j; KAVG_ESTATE when off */
 
+/* Deferred weight updates (KAVG_BF16).  The local step of Algorithm 1, w <- w - (lr/B) sum_s grad F(w; xi_s),
+ * changes a layer's weights by the rank-B term -lr dZ^T A.  With a refresh period m > 1 the stored
+ * replicas are brought up to date only every m local steps (and at the end of kavg_local_steps), by one
+ * product over the m*B samples; between refreshes every product with the current weights is formed as
+ * the product with the stored weights plus the pending terms, e.g. forward
+ *     A W_k^T = A W_0^T - lr sum_{i<k} (A A_i^T) dZ_i ,
+ * whose inner factors are only B x B per pending step.  The iterates are those of Algorithm 1 in exact
+ * arithmetic; in bf16 the pending terms enter unrounded instead of through a re-rounded weight matrix,
+ * and the inner factors are rounded to bf16.  A thin last layer (at most 16 classes) keeps being stepped
+ * at once; biases always are.  m = 1 (default) is the plain path.  Pays when m*B is small against the
+ * layer widths; needs the activations and dZ of m steps.
+ * history_dev: device block of kavg_refresh_bytes(ctx, m) bytes, 256-byte aligned, BORROWED until
+ * kavg_destroy or until m is set back to 1.  Waits for the stream.
+ * Errors: KAVG_EINVAL (m outside [1, K], KAVG_FP32 context, null / misaligned block), KAVG_ENOMEM
+ * (block too small), KAVG_ESTATE (learner-level momentum is on). */
+size_t kavg_refresh_bytes(const kavg_ctx* ctx, int refresh);     /* 0 on bad arguments or refresh < 2 */
+int kavg_set_refresh(kavg_ctx* ctx, int refresh, void* history_dev, size_t bytes);
+
 /* Measurement aid for callers that report per-kernel time (not part of the
  * method): while a class's bit is set in class_mask, one launch in `every` of
  * that class (the first, the every+1-th, ...) is bracketed by a HIP event pair
@@ -185,7 +203,8 @@ int kavg_velocity(kavg_ctx* ctx, int j, float* out_host, size_t n);   /* u^j; KA
 #define KAVG_CLASS_UPDATE   4   /* per-layer weight gradient + SGD update  */
 #define KAVG_CLASS_META     5   /* fused meta step                         */
 #define KAVG_CLASS_HEAD     6   /* last layer with <= 16 classes: forward + loss + data gradient, and its update */
-#define KAVG_NCLASS         7
+#define KAVG_CLASS_CORRECTION 7  /* deferred updates: the low-rank terms of forward and backward products */
+#define KAVG_NCLASS         8
 int kavg_profile(kavg_ctx* ctx, unsigned class_mask, unsigned every);
 int kavg_profile_read(kavg_ctx* ctx, double* ms_out, long long* launches_out);
 

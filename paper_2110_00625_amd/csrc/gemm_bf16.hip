@@ -84,7 +84,17 @@ struct Args {
     float lr;
     float* u; float* ub; float beta;             // velocities of weights / bias (stride w_lstride), null: plain SGD
     const int32_t* next_gather;                  // rows of C's data set that the next step gathers (stride C.gstride), or null
+    // Variants of the epilogues used when weight updates are deferred (see kavg_internal.h, DeferredCall):
+    //   forward mode:  EPI_GRAM   out = bf16(alpha * acc), no bias, no ReLU
+    //   backward mode: EPI_RAW    out = fp32 acc (no mask)
+    //                  EPI_RELU   out = bf16(relu(base + acc));  EPI_LOGITS  out = fp32 (base + acc)
+    //                  EPI_STD with base != null: out = bf16(mask(base + acc))
+    //   update mode:   skip_bias  leave the bias alone (it has been stepped already)
+    int epi; float alpha;
+    const float* base; size_t base_lstride; int ld_base;
+    int skip_bias;
 };
+enum { EPI_STD = 0, EPI_GRAM = 1, EPI_RAW = 2, EPI_RELU = 3, EPI_LOGITS = 4 };
 
 __device__ __forceinline__ uint16_t bf16_bits(float x) {
     __bf16 h = (__bf16)x;                         // round to nearest even
@@ -426,6 +436,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
         const uint16_t* bl = a.bias_lo + (size_t)learner * a.bias_lstride;
         const int c = c0 + (wc * MC + j) * 32 + q * 8 + (lane >> 5) * 4;
         h = (u32x2){0u, 0u}; l = (u32x2){0u, 0u};
+        if (!a.bias_hi) return;                   // product without a bias term
         if (c + 4 <= a.nC) {                      // four columns at once (the planes are 8-byte aligned there)
             h = *(const u32x2*)(bh + c); l = *(const u32x2*)(bl + c);
         } else {                                  // ragged end: column by column, zeros beyond the layer
@@ -447,7 +458,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
         const int r = r0 + (wr * MR + i) * 32 + (lane & 31);
         const int c = c0 + (wc * MC + j) * 32 + q * 8 + (lane >> 5) * 4;
         u32x2 m = {0u, 0u};
-        if (r < a.nR && c < a.nC)
+        if (a.act_prev && r < a.nR && c < a.nC)
             m = *(const u32x2*)(a.act_prev + (size_t)learner * a.act_lstride + (size_t)r * a.ld_act + c);
         return m;
     };
@@ -610,7 +621,10 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                         if (EARLY) { bh2 = ebh[q]; bl2 = ebl[q]; } else bias_raw(j, q, bh2, bl2);
                         const f32x4 bq = bias_join(bh2, bl2);
                         v0 += bq.x; v1 += bq.y; v2 += bq.z; v3 += bq.w;
-                        if (a.relu) {
+                        if (a.epi == EPI_GRAM) {
+                            u32x2 o = {pack2(a.alpha * v0, a.alpha * v1), pack2(a.alpha * v2, a.alpha * v3)};
+                            *(u32x2*)((uint16_t*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
+                        } else if (a.relu) {
                             u32x2 o = {pack2(fmaxf(v0, 0.f), fmaxf(v1, 0.f)), pack2(fmaxf(v2, 0.f), fmaxf(v3, 0.f))};
                             *(u32x2*)((uint16_t*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
                         } else {
@@ -619,12 +633,25 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                         }
                     } else {
                         if (c >= a.nC) continue;
-                        const u32x2 m = EARLY ? emask[q] : mask_of(i, j, q);
-                        // stored activations are relu outputs (never negative): positive <=> non-zero magnitude
-                        v0 = (m.x & 0x7FFFu) ? v0 : 0.f;
-                        v1 = (m.x & 0x7FFF0000u) ? v1 : 0.f;
-                        v2 = (m.y & 0x7FFFu) ? v2 : 0.f;
-                        v3 = (m.y & 0x7FFF0000u) ? v3 : 0.f;
+                        if (a.base) {
+                            const f32x4 bs = *(const f32x4*)(a.base + (size_t)learner * a.base_lstride + (size_t)r * a.ld_base + c);
+                            v0 += bs.x; v1 += bs.y; v2 += bs.z; v3 += bs.w;
+                        }
+                        if (a.epi == EPI_RAW || a.epi == EPI_LOGITS) {
+                            f32x4 o = {v0, v1, v2, v3};
+                            *(f32x4*)((float*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
+                            continue;
+                        }
+                        if (a.epi == EPI_RELU) {
+                            v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f);
+                        } else {
+                            const u32x2 m = EARLY ? emask[q] : mask_of(i, j, q);
+                            // stored activations are relu outputs (never negative): positive <=> non-zero magnitude
+                            v0 = (m.x & 0x7FFFu) ? v0 : 0.f;
+                            v1 = (m.x & 0x7FFF0000u) ? v1 : 0.f;
+                            v2 = (m.y & 0x7FFFu) ? v2 : 0.f;
+                            v3 = (m.y & 0x7FFF0000u) ? v3 : 0.f;
+                        }
                         u32x2 o = {pack2(v0, v1), pack2(v2, v3)};
                         *(u32x2*)((uint16_t*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
                     }
@@ -688,7 +715,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                 }
             }
         }
-        if (tile_c == 0 && tid < TR && r0 + tid < a.nR) {
+        if (!a.skip_bias && tile_c == 0 && tid < TR && r0 + tid < a.nR) {
             const size_t at = (size_t)learner * a.w_lstride + r0 + tid;
             if (a.ub) { bias_sum = a.beta * a.ub[at] + bias_sum; a.ub[at] = bias_sum; }
             const size_t sat = (size_t)learner * a.ws_lstride + r0 + tid;
@@ -766,7 +793,7 @@ hipError_t launch_tiled(const Args& a, int P, int tile, hipStream_t st) {
 hipError_t bf16_forward(const LayerCall& c, hipStream_t st) {
     Args a = {};
     a.R = {(const uint16_t*)c.in, c.gather ? 0 : c.in_stride, c.ld_in, c.gather, c.gather_stride, c.B, c.d_in};
-    a.C = {c.ws, c.ws_stride, c.d_in, nullptr, 0, c.d_out, c.d_in};
+    a.C = {c.ws, c.shared_w ? 0 : c.ws_stride, c.d_in, nullptr, 0, c.d_out, c.d_in};
     a.nR = c.B; a.nC = c.d_out; a.nK = c.d_in;
     a.bias_hi = c.bhi; a.bias_lo = c.blo; a.bias_lstride = c.ws_stride;
     a.out = c.out; a.out_lstride = c.out_stride; a.ld_out = c.ld_out; a.relu = c.relu;
@@ -776,18 +803,21 @@ hipError_t bf16_forward(const LayerCall& c, hipStream_t st) {
 hipError_t bf16_backward_data(const LayerCall& c, hipStream_t st) {
     Args a = {};
     a.R = {(const uint16_t*)c.dz, c.dz_stride, c.ld_dz, nullptr, 0, c.B, round8(c.d_out)};
-    a.C = {c.ws, c.ws_stride, c.d_in, nullptr, 0, c.d_out, c.d_in};      // memory row = k: Cm(c, k) = W[k][c]
+    a.C = {c.ws, c.shared_w ? 0 : c.ws_stride, c.d_in, nullptr, 0, c.d_out, c.d_in};      // memory row = k: Cm(c, k) = W[k][c]
     a.nR = c.B; a.nC = c.d_in; a.nK = c.d_out;
     a.act_prev = (const uint16_t*)c.in; a.act_lstride = c.in_stride; a.ld_act = c.ld_in;
     a.out = c.dz_prev; a.out_lstride = c.dz_prev_stride; a.ld_out = c.ld_in;
+    if (c.bwd_raw) { a.epi = EPI_RAW; a.act_prev = nullptr; }
     return launch_tiled<MODE_BWD, false, true>(a, c.P, pick_tile(MODE_BWD, a.nR, a.nC, c.P), st);
 }
 
 hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     Args a = {};
-    a.R = {(const uint16_t*)c.dz, c.dz_stride, c.ld_dz, nullptr, 0, c.B, c.ld_dz};         // memory row = k: R(r, k) = dZ[k][r]
-    a.C = {(const uint16_t*)c.in, c.gather ? 0 : c.in_stride, c.ld_in, c.gather, c.gather_stride, c.B, c.d_in};
-    a.nR = c.d_out; a.nC = c.d_in; a.nK = c.B;
+    const int rows = c.rows ? c.rows : c.B;
+    a.R = {(const uint16_t*)c.dz, c.dz_stride, c.ld_dz, nullptr, 0, rows, c.ld_dz};         // memory row = k: R(r, k) = dZ[k][r]
+    a.C = {(const uint16_t*)c.in, c.gather ? 0 : c.in_stride, c.ld_in, c.gather, c.gather_stride, rows, c.d_in};
+    a.nR = c.d_out; a.nC = c.d_in; a.nK = rows;
+    a.skip_bias = c.skip_bias;
     a.ws = c.ws; a.wlo = c.wlo; a.ws_lstride = c.ws_stride; a.bhi = c.bhi; a.blo = c.blo; a.w_lstride = c.w_stride;
     a.lr = c.lr; a.u = c.u; a.ub = c.ub; a.beta = c.beta;
     a.next_gather = c.gather ? c.next_gather : nullptr;
@@ -798,7 +828,7 @@ hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
         if (c.gather) return launch<MODE_UPD, 128, 64, 4, 1, 1, 64, true, true, PIPE_PLAIN, true, true>(a, c.P, st);
         return launch<MODE_UPD, 128, 64, 4, 1, 1, 64, true, true, PIPE_PLAIN, true, false>(a, c.P, st);
     }
-    if (c.B > 128) {
+    if (rows > 128) {
         // Long contractions: per output tile the two operands (read out of the L2 cache, B rows each) weigh as
         // much as the master tile itself, and a compute unit can only pull so many bytes per clock; a
         // 128x128 tile reads a third less of them per weight (large: 15.0 -> 14.5 ms per round).
@@ -807,6 +837,56 @@ hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     }
     if (c.gather) return launch<MODE_UPD, 64, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, true>(a, c.P, st);
     return launch<MODE_UPD, 64, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, false>(a, c.P, st);
+}
+
+hipError_t bf16_gram(const GramCall& c, hipStream_t st) {
+    Args a = {};
+    a.R = {(const uint16_t*)c.R, c.R_gather ? 0 : c.R_stride, c.ldR, c.R_gather, c.R_gstride, c.nR, round8(c.nK)};
+    a.C = {(const uint16_t*)c.C, c.C_gather ? 0 : c.C_stride, c.ldC, c.C_gather, c.C_gstride, c.nC, round8(c.nK)};
+    a.nR = c.nR; a.nC = c.nC; a.nK = c.nK;
+    a.out = c.out; a.out_lstride = c.out_stride; a.ld_out = c.ld_out; a.relu = 1;
+    a.epi = EPI_GRAM; a.alpha = c.alpha;
+    return launch_tiled<MODE_FWD, false, false>(a, c.P, pick_tile(MODE_FWD, a.nR, a.nC, c.P), st);
+}
+
+hipError_t bf16_apply(const ApplyCall& c, hipStream_t st) {
+    Args a = {};
+    a.R = {(const uint16_t*)c.S, c.S_stride, c.ldS, nullptr, 0, c.nR, round8(c.nK)};
+    a.C = {(const uint16_t*)c.M, c.M_stride, c.ldM, nullptr, 0, c.nK, c.nC_cont};      // memory row = k
+    a.nR = c.nR; a.nC = c.nC; a.nK = c.nK;
+    a.base = c.base; a.base_lstride = c.base_stride; a.ld_base = c.ld_base;
+    a.out = c.out; a.out_lstride = c.out_stride; a.ld_out = c.ld_out;
+    if (c.epi == KAVG_APPLY_MASK) {
+        a.epi = EPI_STD; a.act_prev = (const uint16_t*)c.act; a.act_lstride = c.act_stride; a.ld_act = c.ld_act;
+    } else {
+        a.epi = c.epi == KAVG_APPLY_RELU ? EPI_RELU : EPI_LOGITS;
+    }
+    return launch_tiled<MODE_BWD, false, true>(a, c.P, pick_tile(MODE_BWD, a.nR, a.nC, c.P), st);
+}
+
+namespace {
+// one lane per (learner, unit): the column of dZ is summed over the step's rows in ascending order
+__global__ void __launch_bounds__(256) bias_step_kernel(uint16_t* bhi, uint16_t* blo, size_t b_stride, const uint16_t* dz,
+                                                        int ld_dz, size_t dz_stride, int rows, int d, float lr) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    const int learner = blockIdx.y;
+    if (c >= d) return;
+    const uint16_t* p = dz + (size_t)learner * dz_stride + c;
+    float sum = 0.f;
+#pragma unroll 8
+    for (int r = 0; r < rows; ++r) sum += bf16_to_f32(p[(size_t)r * ld_dz]);
+    const size_t at = (size_t)learner * b_stride + c;
+    const float b = __builtin_bit_cast(float, split_join(bhi[at], blo[at])) - lr * sum;
+    bhi[at] = (uint16_t)split_hi(__builtin_bit_cast(uint32_t, b));
+    blo[at] = (uint16_t)split_lo(__builtin_bit_cast(uint32_t, b));
+}
+}  // namespace
+
+hipError_t launch_bias_step(uint16_t* bhi, uint16_t* blo, size_t b_stride, const void* dz, int ld_dz,
+                            size_t dz_stride, int P, int rows, int d, float lr, hipStream_t st) {
+    hipLaunchKernelGGL(bias_step_kernel, dim3((d + 255) / 256, P), dim3(256), 0, st, bhi, blo, b_stride,
+                       (const uint16_t*)dz, ld_dz, dz_stride, rows, d, lr);
+    return hipGetLastError();
 }
 
 }  // namespace kavg

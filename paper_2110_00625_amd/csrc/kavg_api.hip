@@ -108,6 +108,13 @@ static __device__ __align__(256) unsigned char scratch[KAVG_STATIC_WORKSPACE_BYT
     } catch (const std::bad_alloc&) { return fail(ctx, KAVG_ENOMEM, "host allocation failed"); } \
     catch (...) { return fail(ctx, KAVG_ENOMEM, "unexpected host failure"); }
 
+// carve-up of the history block of deferred weight updates (kavg_set_refresh)
+struct HistoryLayout {
+    std::vector<size_t> act, dz;        // per layer l = 1..L (index l-1): activations leaving / dZ of the layer, [P][m*B][ld]
+    size_t z0 = 0, s = 0, total = 0;    // fp32 [P][B][maxld]; bf16 [P][B][ldS]
+    int ldS = 0, maxld = 0;
+};
+
 struct kavg_ctx {
     int P, K, B, L, dtype;
     float lr, mu;
@@ -123,6 +130,7 @@ struct kavg_ctx {
     uint32_t t0;          // local steps every learner has taken
     uint64_t round;
     bool have_params, have_steps;
+    bool replicas_equal = false;   // every replica holds the global model (no local step since the last rebroadcast)
     float beta;           // learner-level momentum, 0 = off
     float* vel;           // [P][stride] velocities, caller memory, null = off
     char err[256];
@@ -138,6 +146,10 @@ struct kavg_ctx {
     bool graph_on = false;
     bool warm = false;                  // the sequence has run eagerly once with the current pointers
     hipGraphExec_t gexec = nullptr;
+    // deferred weight updates (kavg_set_refresh): history block, its carve-up, refresh period
+    int refresh = 1;
+    char* hist = nullptr;
+    HistoryLayout hl;
     int static_dev = -1;                // >= 0: the context works in the library's own workspace of that device
 
     float* w_tilde() const { return (float*)(ws + lo.off_w); }
@@ -200,6 +212,7 @@ int install_global(kavg_ctx* c, const float* w_host, const float* v_host) {
     KAVG_HIP(c, hipStreamSynchronize(c->stream));   // host buffers may be reused by the caller
     c->have_params = true;
     c->have_steps = false;
+    c->replicas_equal = true;
     return KAVG_OK;
 }
 
@@ -412,7 +425,10 @@ namespace {
 // The K local steps of every learner after the indices are in place, and the per-step loss means.
 // All arguments are fixed between calls (workspace pointers, data pointers, shapes), which is what
 // lets kavg_local_steps replay this sequence as a graph.
+int issue_steps_deferred(kavg_ctx* c);
+
 int issue_steps(kavg_ctx* c) {
+    if (c->refresh > 1) return issue_steps_deferred(c);
     hipStream_t st = c->stream;
     const bool bf = c->dtype == KAVG_BF16;
     const int L = c->L;
@@ -435,7 +451,7 @@ int issue_steps(kavg_ctx* c) {
         } else {
             Bracket br(c, KAVG_CLASS_LOSS);
             KAVG_HIP(c, launch_softmax_ce(c->logits(), c->lo.ldz, c->dims[L], c->y, idx_k, idx_ls, c->B, c->P,
-                                          c->ws + c->lo.off_dz[L - 1], bf ? 1 : 0, rowloss_k, st));
+                                          c->ws + c->lo.off_dz[L - 1], (long)c->B * c->lo.ldz, bf ? 1 : 0, rowloss_k, st));
         }
         for (int l = L; l >= 1; --l) {                       // backward; W_l is read before it is updated
             LayerCall q = layer_call(c, l, k);
@@ -455,6 +471,178 @@ int issue_steps(kavg_ctx* c) {
     {
         Bracket br(c, KAVG_CLASS_LOSS);
         KAVG_HIP(c, launch_loss_mean(c->rowloss(), c->losses(), c->K * c->P, c->B, st));
+    }
+    return KAVG_OK;
+}
+
+// ---- deferred weight updates ----------------------------------------------------------------
+// Algorithm 1's local step adds -lr dZ_k^T A_k to the learner's weights.  With a refresh period m > 1
+// the stored replica is only brought up to date every m steps (one product over m*B samples instead
+// of m read-modify-write passes over the master); in between, a product with the current weights
+// W_k = W_0 - lr sum_{i<k} dZ_i^T A_i is formed as the product with the stored W_0 plus
+//     forward:        - lr (A  H^T) G        H = [A_0; ..; A_{k-1}] inputs of the layer, G = [dZ_0; ..] its dZ
+//     backward-data:  - lr (dZ G^T) H
+// where the inner factors are B x kB matrices.  Activations and dZ of the steps since the last refresh
+// are kept (the per-step buffers become slots of [P][m*B][d] histories); biases are stepped at once.
+extern "C++" HistoryLayout history_layout(const kavg_ctx* c, int m) {
+    HistoryLayout h;
+    const int L = c->L;
+    size_t p = 0;
+    auto take = [&](size_t bytes) { size_t at = p; p = round_up(p + bytes, ALIGN); return at; };
+    h.act.assign(L, 0);
+    h.dz.assign(L, 0);
+    h.maxld = c->lo.ldz;
+    for (int l = 1; l <= L; ++l) {
+        const size_t ld = l == L ? (size_t)c->lo.ldz : (size_t)c->dims[l];
+        if ((int)ld > h.maxld) h.maxld = (int)ld;
+        if (l < L) h.act[l - 1] = take((size_t)c->P * m * c->B * ld * 2);
+        h.dz[l - 1] = take((size_t)c->P * m * c->B * ld * 2);
+    }
+    // the fp32 buffer also receives raw backward products, as wide as the widest layer input it flows into
+    for (int l = 1; l < L; ++l) if (c->dims[l] > h.maxld) h.maxld = c->dims[l];
+    h.ldS = (int)round_up((size_t)m * c->B, 8);
+    h.z0 = take((size_t)c->P * c->B * h.maxld * 4);
+    h.s = take((size_t)c->P * c->B * h.ldS * 2);
+    h.total = p;
+    return h;
+}
+
+int issue_steps_deferred(kavg_ctx* c) {
+    hipStream_t st = c->stream;
+    const int L = c->L, P = c->P, B = c->B, K = c->K, m = c->refresh;
+    const Layout& lo = c->lo;
+    const bool head = head_supported(c->dims[L]);
+    const int Lw = head ? L - 1 : L;                  // layers whose weights are kept deferred
+    auto ld_of = [&](int l) { return l == L ? lo.ldz : c->dims[l]; };
+    auto actH = [&](int l, int slot) { return c->hist + c->hl.act[l - 1] + (size_t)slot * B * c->dims[l] * 2; };
+    auto dzH = [&](int l, int slot) { return c->hist + c->hl.dz[l - 1] + (size_t)slot * B * ld_of(l) * 2; };
+    float* z0 = (float*)(c->hist + c->hl.z0);
+    uint16_t* S = (uint16_t*)(c->hist + c->hl.s);
+    const size_t z0_stride = (size_t)B * c->hl.maxld, S_stride = (size_t)B * c->hl.ldS;
+    const long idx_ls = (long)K * B;
+
+    // the launch description of layer l at step k, operands in their history slots
+    auto call = [&](int l, int k, int slot) {
+        LayerCall q = {};
+        q.P = P; q.B = B; q.d_in = c->dims[l - 1]; q.d_out = c->dims[l];
+        q.w_stride = lo.stride; q.ws_stride = lo.stride;
+        q.ws = c->hi_planes() + lo.w_off[l - 1];  q.wlo = c->lo_planes() + lo.w_off[l - 1];
+        q.bhi = c->hi_planes() + lo.b_off[l - 1]; q.blo = c->lo_planes() + lo.b_off[l - 1];
+        q.shadow_cached = shadows_stay_cached(P, lo.stride);
+        if (l == 1) {
+            q.in = c->X; q.ld_in = c->dims[0]; q.in_stride = 0;
+            q.gather = c->idx() + (size_t)k * B; q.gather_stride = idx_ls;
+        } else {
+            q.in = actH(l - 1, slot); q.ld_in = c->dims[l - 1]; q.in_stride = (size_t)m * B * q.ld_in;
+            q.dz_prev = dzH(l - 1, slot); q.dz_prev_stride = (size_t)m * B * q.ld_in;
+        }
+        if (l < L) { q.out = actH(l, slot); q.ld_out = c->dims[l]; q.out_stride = (size_t)m * B * q.ld_out; q.relu = 1; }
+        else { q.out = c->logits(); q.ld_out = lo.ldz; q.out_stride = (size_t)B * lo.ldz; q.relu = 0; }
+        q.dz = dzH(l, slot); q.ld_dz = ld_of(l); q.dz_stride = (size_t)m * B * q.ld_dz;
+        q.lr = c->lr;
+        // until the first refresh of a round every stored replica still holds the global model: all
+        // learners then read learner 0's copy, which the caches serve, instead of P copies from memory
+        q.shared_w = (c->replicas_equal && k < m) ? 1 : 0;
+        return q;
+    };
+
+    for (int k = 0; k < K; ++k) {
+        const int slot = k % m, cnt = slot;           // cnt steps' updates are pending
+        const int32_t* idx_k = c->idx() + (size_t)k * B;
+        const int32_t* idx_hist = c->idx() + (size_t)(k - cnt) * B;      // rows of the pending steps, cnt*B per learner
+        float* rowloss_k = c->rowloss() + (size_t)k * P * B;
+        for (int l = 1; l <= Lw; ++l) {                                  // forward
+            LayerCall q = call(l, k, slot);
+            if (cnt == 0) {
+                Bracket br(c, KAVG_CLASS_FORWARD);
+                KAVG_HIP(c, bf16_forward(q, st));
+                continue;
+            }
+            const int ld = ld_of(l);
+            {
+                Bracket br(c, KAVG_CLASS_FORWARD);
+                LayerCall q0 = q;                                        // stored weights, bias included, fp32
+                q0.out = z0; q0.ld_out = ld; q0.out_stride = z0_stride; q0.relu = 0;
+                KAVG_HIP(c, bf16_forward(q0, st));
+            }
+            Bracket br(c, KAVG_CLASS_CORRECTION);
+            GramCall g = {};
+            g.P = P; g.nR = B; g.nC = cnt * B; g.nK = q.d_in;
+            g.R = q.in; g.ldR = q.ld_in; g.R_stride = q.in_stride; g.R_gather = q.gather; g.R_gstride = idx_ls;
+            g.ldC = q.ld_in;
+            if (l == 1) { g.C = c->X; g.C_stride = 0; g.C_gather = idx_hist; g.C_gstride = idx_ls; }
+            else { g.C = actH(l - 1, 0); g.C_stride = q.in_stride; }
+            g.out = S; g.ld_out = c->hl.ldS; g.out_stride = S_stride; g.alpha = -c->lr;
+            KAVG_HIP(c, bf16_gram(g, st));
+            ApplyCall ap = {};
+            ap.P = P; ap.nR = B; ap.nC = ld; ap.nC_cont = ld; ap.nK = cnt * B;
+            ap.S = S; ap.ldS = c->hl.ldS; ap.S_stride = S_stride;
+            ap.M = dzH(l, 0); ap.ldM = ld; ap.M_stride = (size_t)m * B * ld;
+            ap.base = z0; ap.ld_base = ld; ap.base_stride = z0_stride;
+            ap.epi = l < L ? KAVG_APPLY_RELU : KAVG_APPLY_LOGITS;
+            ap.out = q.out; ap.ld_out = q.ld_out; ap.out_stride = q.out_stride;
+            KAVG_HIP(c, bf16_apply(ap, st));
+        }
+        if (head) {
+            LayerCall q = call(L, k, slot);
+            Bracket br(c, KAVG_CLASS_HEAD);
+            KAVG_HIP(c, head_forward_backward(q, c->y, idx_k, idx_ls, rowloss_k, 1, st));
+        } else {
+            Bracket br(c, KAVG_CLASS_LOSS);
+            KAVG_HIP(c, launch_softmax_ce(c->logits(), lo.ldz, c->dims[L], c->y, idx_k, idx_ls, B, P, dzH(L, slot),
+                                          (long)m * B * lo.ldz, 1, rowloss_k, st));
+        }
+        for (int l = L; l >= 1; --l) {                                   // backward
+            LayerCall q = call(l, k, slot);
+            if (head && l == L) {
+                Bracket br(c, KAVG_CLASS_HEAD);
+                KAVG_HIP(c, head_update(q, idx_k, idx_ls, 1, st));       // the thin last layer is stepped at once
+                continue;
+            }
+            if (l > 1) {
+                if (cnt == 0) {
+                    Bracket br(c, KAVG_CLASS_BACKWARD);
+                    KAVG_HIP(c, bf16_backward_data(q, st));
+                } else {
+                    {
+                        Bracket br(c, KAVG_CLASS_BACKWARD);
+                        LayerCall q0 = q;
+                        q0.bwd_raw = 1; q0.dz_prev = z0; q0.dz_prev_stride = z0_stride;
+                        KAVG_HIP(c, bf16_backward_data(q0, st));
+                    }
+                    Bracket br(c, KAVG_CLASS_CORRECTION);
+                    GramCall g = {};
+                    g.P = P; g.nR = B; g.nC = cnt * B; g.nK = q.ld_dz;
+                    g.R = q.dz; g.ldR = q.ld_dz; g.R_stride = q.dz_stride;
+                    g.C = dzH(l, 0); g.ldC = q.ld_dz; g.C_stride = q.dz_stride;
+                    g.out = S; g.ld_out = c->hl.ldS; g.out_stride = S_stride; g.alpha = -c->lr;
+                    KAVG_HIP(c, bf16_gram(g, st));
+                    ApplyCall ap = {};
+                    ap.P = P; ap.nR = B; ap.nC = q.ld_in; ap.nC_cont = q.ld_in; ap.nK = cnt * B;
+                    ap.S = S; ap.ldS = c->hl.ldS; ap.S_stride = S_stride;
+                    ap.M = actH(l - 1, 0); ap.ldM = q.ld_in; ap.M_stride = q.in_stride;
+                    ap.base = z0; ap.ld_base = q.ld_in; ap.base_stride = z0_stride;
+                    ap.epi = KAVG_APPLY_MASK; ap.act = q.in; ap.ld_act = q.ld_in; ap.act_stride = q.in_stride;
+                    ap.out = q.dz_prev; ap.ld_out = q.ld_in; ap.out_stride = q.dz_prev_stride;
+                    KAVG_HIP(c, bf16_apply(ap, st));
+                }
+            }
+            Bracket br(c, KAVG_CLASS_UPDATE);
+            KAVG_HIP(c, launch_bias_step(q.bhi, q.blo, lo.stride, q.dz, q.ld_dz, q.dz_stride, P, B, q.d_out, c->lr, st));
+        }
+        if (slot == m - 1 || k == K - 1) {                               // bring the stored replicas up to date
+            for (int l = 1; l <= Lw; ++l) {
+                LayerCall q = call(l, k, 0);
+                q.rows = (slot + 1) * B; q.skip_bias = 1;
+                if (l == 1) q.gather = idx_hist;
+                Bracket br(c, KAVG_CLASS_UPDATE);
+                KAVG_HIP(c, bf16_update(q, st));
+            }
+        }
+    }
+    {
+        Bracket br(c, KAVG_CLASS_LOSS);
+        KAVG_HIP(c, launch_loss_mean(c->rowloss(), c->losses(), K * P, B, st));
     }
     return KAVG_OK;
 }
@@ -509,6 +697,7 @@ int kavg_local_steps(kavg_ctx* c) {
     }
     c->t0 += (uint32_t)c->K;
     c->have_steps = true;
+    c->replicas_equal = false;
     return KAVG_OK;
     KAVG_NOTHROW_END(c)
 }
@@ -528,6 +717,7 @@ int kavg_meta_update(kavg_ctx* c) {
                                            c->P, c->lo.n, c->mu, 0, c->stream));
     }
     c->round += 1;
+    c->replicas_equal = true;
     return KAVG_OK;
     KAVG_NOTHROW_END(c)
 }
@@ -644,6 +834,7 @@ int kavg_set_learner_momentum(kavg_ctx* c, float beta, void* velocity_dev, size_
         drop_graph(c);
         return KAVG_OK;
     }
+    if (c->refresh > 1) return fail(c, KAVG_ESTATE, "deferred updates and learner-level momentum exclude each other");
     if (((uintptr_t)velocity_dev % ALIGN) != 0) return fail(c, KAVG_EINVAL, "velocity buffer must be 256-byte aligned");
     if (bytes < kavg_velocity_bytes(c)) return fail(c, KAVG_ENOMEM, "velocity buffer has %zu bytes, %zu needed", bytes, kavg_velocity_bytes(c));
     KAVG_HIP(c, hipMemsetAsync(velocity_dev, 0, kavg_velocity_bytes(c), c->stream));
@@ -659,6 +850,33 @@ int kavg_velocity(kavg_ctx* c, int j, float* out_host, size_t n) {
     if (!c->vel) return fail(c, KAVG_ESTATE, "learner-level momentum is off");
     KAVG_HIP(c, hipMemcpyAsync(out_host, c->vel + (size_t)j * c->lo.stride, n * 4, hipMemcpyDeviceToHost, c->stream));
     return sync_and_check(c);
+}
+
+size_t kavg_refresh_bytes(const kavg_ctx* c, int refresh) {
+    if (!c || refresh < 2 || refresh > c->K || c->dtype != KAVG_BF16) return 0;
+    try { return history_layout(c, refresh).total; } catch (...) { return 0; }
+}
+
+int kavg_set_refresh(kavg_ctx* c, int refresh, void* history_dev, size_t bytes) {
+    if (!c) return KAVG_EINVAL;
+    KAVG_NOTHROW_BEGIN
+    if (refresh < 1 || refresh > c->K) return fail(c, KAVG_EINVAL, "refresh period must lie in [1, K]");
+    KAVG_HIP(c, hipStreamSynchronize(c->stream));
+    if (refresh == 1) {
+        c->refresh = 1; c->hist = nullptr;
+        drop_graph(c);
+        return KAVG_OK;
+    }
+    if (c->dtype != KAVG_BF16) return fail(c, KAVG_EINVAL, "deferred updates are built for KAVG_BF16 only");
+    if (c->vel) return fail(c, KAVG_ESTATE, "deferred updates and learner-level momentum exclude each other");
+    if (!history_dev || ((uintptr_t)history_dev % ALIGN) != 0)
+        return fail(c, KAVG_EINVAL, "history block must be a non-null, 256-byte aligned device pointer");
+    HistoryLayout h = history_layout(c, refresh);
+    if (bytes < h.total) return fail(c, KAVG_ENOMEM, "history block has %zu bytes, %zu needed", bytes, h.total);
+    c->hl = h; c->refresh = refresh; c->hist = (char*)history_dev;
+    drop_graph(c);
+    return KAVG_OK;
+    KAVG_NOTHROW_END(c)
 }
 
 uint64_t kavg_round(const kavg_ctx* c) { return c ? c->round : 0; }

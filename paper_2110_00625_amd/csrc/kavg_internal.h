@@ -35,11 +35,11 @@ hipError_t launch_broadcast(const float* w_tilde, float* reps, size_t stride,
                             uint16_t* shadow, size_t sstride, int P, size_t n, hipStream_t st);
 
 // ---- loss and its gradient ----
-// logits [P][B][ldz] fp32; labels y[idx[j][m]]; dz [P][B][ldz] (fp32 or bf16), pad columns zeroed;
-// rowloss [P][B].  dZ = (softmax - onehot)/B.
+// logits [P][B][ldz] fp32; labels y[idx[j][m]]; dz: learner j's B rows of ldz at dz + j*dz_learner_stride
+// (fp32 or bf16), pad columns zeroed; rowloss [P][B].  dZ = (softmax - onehot)/B.
 hipError_t launch_softmax_ce(const float* logits, int ldz, int C, const int32_t* y,
                              const int32_t* idx, long idx_learner_stride, int B, int P,
-                             void* dz, int dz_bf16, float* rowloss, hipStream_t st);
+                             void* dz, long dz_learner_stride, int dz_bf16, float* rowloss, hipStream_t st);
 // losses[k][j] = mean_m rowloss[k][j][m]
 hipError_t launch_loss_mean(const float* rowloss, float* losses, int KP, int B, hipStream_t st);
 
@@ -74,7 +74,43 @@ struct LayerCall {
     // learner-level momentum: velocity of this layer's weights (learner 0; stride w_stride) and of its
     // bias, null when off.  u <- beta u + g, w <- w - lr u.
     float* u; float* ub; float beta;
+    // deferred weight updates (bf16 mode):
+    int shared_w;          // forward / backward-data: every learner's stored weights equal learner 0's (round start): read those
+    int bwd_raw;           // backward-data: write the unmasked fp32 product to dz_prev instead of the masked bf16 one
+    int rows;              // update: rows of dz / in to contract over (0: B) -- the steps since the last refresh
+    int skip_bias;         // update: leave the bias alone (it is stepped after every local step)
 };
+
+// ---- deferred weight updates (Algorithm 1: every local step adds a rank-B term -lr dZ^T A to the
+// learner's weights; between two refreshes of the stored replica the products use the stored
+// weights plus those terms, W_k x = W_0 x - lr sum_i dZ_i^T (A_i x)) ----
+// out[j][r][c] = bf16(alpha * sum_k R[j][r][k] * C[j][c][k]); R, C bf16 with k contiguous; either may be
+// gathered rows of a shared matrix (stride 0, gather != null)
+struct GramCall {
+    int P, nR, nC, nK;
+    const void* R; int ldR; size_t R_stride; const int32_t* R_gather; long R_gstride;
+    const void* C; int ldC; size_t C_stride; const int32_t* C_gather; long C_gstride;
+    void* out; int ld_out; size_t out_stride;
+    float alpha;
+};
+// out[j][r][c] = epi(base[j][r][c] + sum_h S[j][r][h] * M[j][h][c]); S bf16 [nR][ldS], M bf16 [nK][ldM],
+// base fp32.  epi: KAVG_APPLY_RELU -> bf16 relu; KAVG_APPLY_LOGITS -> fp32; KAVG_APPLY_MASK -> bf16,
+// zero where act[j][r][c] <= 0.  nC_cont: readable columns of M (multiple of 8, >= nC).
+enum { KAVG_APPLY_RELU = 0, KAVG_APPLY_LOGITS = 1, KAVG_APPLY_MASK = 2 };
+struct ApplyCall {
+    int P, nR, nC, nC_cont, nK;
+    const void* S; int ldS; size_t S_stride;
+    const void* M; int ldM; size_t M_stride;
+    const float* base; int ld_base; size_t base_stride;
+    int epi;
+    const void* act; int ld_act; size_t act_stride;
+    void* out; int ld_out; size_t out_stride;
+};
+hipError_t bf16_gram(const GramCall& c, hipStream_t st);
+hipError_t bf16_apply(const ApplyCall& c, hipStream_t st);
+// b[j][c] -= lr * sum_r dz[j][r][c] on bias planes (split.h); dz bf16 [P][rows][ld_dz]
+hipError_t launch_bias_step(uint16_t* bhi, uint16_t* blo, size_t b_stride, const void* dz, int ld_dz,
+                            size_t dz_stride, int P, int rows, int d, float lr, hipStream_t st);
 
 // fp32 path
 // splits of the forward contraction of a layer and the contraction range of each; shapes only

@@ -95,7 +95,7 @@ template <bool BF16>
 __global__ void __launch_bounds__(256)
 softmax_ce_kernel(const float* __restrict__ logits, int ldz, int C, const int32_t* __restrict__ y,
                   const int32_t* __restrict__ idx, long idx_learner_stride, int B, int P,
-                  void* __restrict__ dz, float* __restrict__ rowloss) {
+                  void* __restrict__ dz, long dz_learner_stride, float* __restrict__ rowloss) {
     const int lane = threadIdx.x & 63;
     const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= (long)P * B) return;                       // whole wavefront leaves together
@@ -103,6 +103,7 @@ softmax_ce_kernel(const float* __restrict__ logits, int ldz, int C, const int32_
     int label = y[idx[(long)j * idx_learner_stride + m]];
     label = label < 0 ? 0 : (label >= C ? C - 1 : label); // labels were validated; never index outside
     const float* z = logits + row * ldz;
+    const long dz_row = (long)j * dz_learner_stride + (long)m * ldz;
 
     float mx = -INFINITY;
     for (int c = lane; c < C; c += 64) mx = fmaxf(mx, z[c]);
@@ -119,9 +120,9 @@ softmax_ce_kernel(const float* __restrict__ logits, int ldz, int C, const int32_
         }
         if (BF16) {
             __bf16 h = (__bf16)g;
-            ((uint16_t*)dz)[row * ldz + c] = __builtin_bit_cast(uint16_t, h);
+            ((uint16_t*)dz)[dz_row + c] = __builtin_bit_cast(uint16_t, h);
         } else {
-            ((float*)dz)[row * ldz + c] = g;
+            ((float*)dz)[dz_row + c] = g;
         }
     }
     if (lane == 0) rowloss[row] = -(z[label] - mx - logf(sum));
@@ -129,15 +130,15 @@ softmax_ce_kernel(const float* __restrict__ logits, int ldz, int C, const int32_
 
 hipError_t launch_softmax_ce(const float* logits, int ldz, int C, const int32_t* y,
                              const int32_t* idx, long idx_learner_stride, int B, int P,
-                             void* dz, int dz_bf16, float* rowloss, hipStream_t st) {
+                             void* dz, long dz_learner_stride, int dz_bf16, float* rowloss, hipStream_t st) {
     long rows = (long)P * B;
     unsigned grid = (unsigned)((rows + 3) / 4);
     if (dz_bf16)
         hipLaunchKernelGGL(softmax_ce_kernel<true>, dim3(grid), dim3(256), 0, st, logits, ldz, C, y,
-                           idx, idx_learner_stride, B, P, dz, rowloss);
+                           idx, idx_learner_stride, B, P, dz, dz_learner_stride, rowloss);
     else
         hipLaunchKernelGGL(softmax_ce_kernel<false>, dim3(grid), dim3(256), 0, st, logits, ldz, C, y,
-                           idx, idx_learner_stride, B, P, dz, rowloss);
+                           idx, idx_learner_stride, B, P, dz, dz_learner_stride, rowloss);
     return hipGetLastError();
 }
 

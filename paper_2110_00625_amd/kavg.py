@@ -20,10 +20,10 @@ EXPORTS = [
     "kavg_set_data", "kavg_set_indices", "kavg_local_steps", "kavg_meta_update", "kavg_params",
     "kavg_momentum", "kavg_replica", "kavg_losses", "kavg_indices", "kavg_round", "kavg_last_error",
     "kavg_destroy", "kavg_meta_update_flat", "kavg_profile", "kavg_profile_read",
-    "kavg_velocity_bytes", "kavg_set_learner_momentum", "kavg_velocity", "kavg_graph", "kavg_init_static", "kavg_probe",
+    "kavg_velocity_bytes", "kavg_set_learner_momentum", "kavg_velocity", "kavg_graph", "kavg_init_static", "kavg_probe", "kavg_refresh_bytes", "kavg_set_refresh",
 ]
 STATIC_WORKSPACE_BYTES = 32 << 20
-CLASS_NAMES = ["index", "forward", "loss", "backward", "update", "meta", "head"]
+CLASS_NAMES = ["index", "forward", "loss", "backward", "update", "meta", "head", "correction"]
 
 
 class KavgError(RuntimeError):
@@ -78,6 +78,7 @@ def load_library():
         "kavg_profile": [c_vp, ctypes.c_uint, ctypes.c_uint],
         "kavg_profile_read": [c_vp, c_vp, c_vp],
         "kavg_graph": [c_vp, c_int],
+        "kavg_set_refresh": [c_vp, c_int, c_vp, c_sz],
         "kavg_meta_update_flat": [c_vp, c_vp, c_vp, c_sz, c_vp, c_sz, c_int, c_sz, c_f, c_vp],
         "kavg_probe": [c_int, c_vp, c_vp, c_sz, c_int, c_vp, c_vp, ctypes.POINTER(ctypes.c_double)],
     }.items():
@@ -86,6 +87,8 @@ def load_library():
         fn.argtypes = args
     lib.kavg_velocity_bytes.restype = c_sz
     lib.kavg_velocity_bytes.argtypes = [c_vp]
+    lib.kavg_refresh_bytes.restype = c_sz
+    lib.kavg_refresh_bytes.argtypes = [c_vp, c_int]
     lib.kavg_round.restype = ctypes.c_uint64
     lib.kavg_round.argtypes = [c_vp]
     lib.kavg_last_error.restype = ctypes.c_char_p
@@ -225,6 +228,20 @@ class MAvg:
 
     def velocity(self, j):
         return self._out(self.lib.kavg_velocity, int(j))
+
+    def set_refresh(self, m):
+        """Bring the stored replicas up to date every m local steps only (1 = every step, the default);
+        allocates the history block."""
+        if m == 1:
+            _check(self.lib, self.ctx, self.lib.kavg_set_refresh(self.ctx, 1, None, 0))
+            self._keep.pop("hist", None)
+            return
+        nbytes = int(self.lib.kavg_refresh_bytes(self.ctx, int(m)))
+        if nbytes == 0:
+            raise KavgError(KAVG_EINVAL, "kavg_refresh_bytes rejected refresh period %d" % m)
+        hist = self._torch.empty(nbytes, dtype=self._torch.uint8, device=self.device)
+        _check(self.lib, self.ctx, self.lib.kavg_set_refresh(self.ctx, int(m), hist.data_ptr(), nbytes))
+        self._keep["hist"] = hist
 
     # -- the hot path -------------------------------------------------------
     def local_steps(self):

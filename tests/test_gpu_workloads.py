@@ -96,7 +96,17 @@ import functools  # noqa: E402
 from paper_2110_00625_amd.configs import CIFAR_MLP, NOISY_WIDE, LARGE, WORKLOADS, num_params  # noqa: E402
 
 TOL_BF16 = 2e-2
-ORACLE_THREADS = 8         # learners the oracle walks at a time (they are independent between meta steps)
+HOST_CORES = 16            # the GPU machine's CPU share
+
+
+def _oracle_local_steps(o, learners=None):
+    """The oracle's K local steps with its learners walked by up to HOST_CORES threads (they are
+    independent between meta steps) and the BLAS pool narrowed so that the two do not oversubscribe."""
+    from threadpoolctl import threadpool_limits
+    n = o.P if learners is None else len(learners)
+    workers = max(1, min(n, HOST_CORES))
+    with threadpool_limits(limits=max(1, HOST_CORES // workers)):
+        o.local_steps(learners=learners, workers=workers)
 
 
 @functools.lru_cache(maxsize=1)
@@ -125,7 +135,7 @@ def test_cifar_mlp_free_running_first_10_rounds():
     g, o = _bf16_pair(w, w.N)
     for r in range(10):
         g.local_steps()
-        o.local_steps(workers=ORACLE_THREADS)
+        _oracle_local_steps(o)
         assert np.array_equal(g.indices(), o.indices())
         if r == 0:
             e = max(replica_error(g.replica(j), o.replica(j), w.dims) for j in range(w.P))
@@ -156,7 +166,7 @@ def test_cifar_mlp_single_rounds_spread_over_all_50():
         g.local_steps()
         g.meta_update()
         if r in checked:
-            o.local_steps(workers=ORACLE_THREADS)
+            _oracle_local_steps(o)
             assert np.array_equal(g.indices(), o.indices())
             o.meta_update()
             e = worst_error(g.params(), o.params(), w.dims)
@@ -184,7 +194,7 @@ def test_big_workloads_one_full_round_every_learner(w):
     steps of every learner, then the meta step; global model within tolerance, tensor by tensor."""
     g, o = _bf16_pair(w, w.N)
     g.local_steps()
-    o.local_steps(workers=ORACLE_THREADS)
+    _oracle_local_steps(o)
     assert np.array_equal(g.indices(), o.indices())
     reps = [replica_error(g.replica(j), o.replica(j), w.dims) for j in range(w.P)]
     print("%s: single replicas after K=%d local steps: median %.3g, worst %.3g" % (
@@ -199,6 +209,18 @@ def test_big_workloads_one_full_round_every_learner(w):
     e = worst_error(g.params(), o.params(), w.dims, verbose=True)
     print("%s: worst %.3g, momentum buffer %.3g" % (w.name, e, flat_error(g.momentum(), o.momentum())))
     assert e < TOL_BF16, "%s: global model after one round: %.3g" % (w.name, e)
+    if w is NOISY_WIDE:
+        # the same round with the stored replicas refreshed once (deferred updates, m = K), against the same oracle
+        g2, _unused = _bf16_pair(w, w.N)
+        g2.set_refresh(w.K)
+        g2.local_steps()
+        assert np.array_equal(g2.indices(), o.indices())
+        g2.meta_update()
+        e2 = worst_error(g2.params(), o.params(), w.dims)
+        print("%s with deferred updates (m = %d): worst %.3g; against the plain path %.3g" % (
+            w.name, w.K, e2, worst_error(g2.params(), g.params(), w.dims)))
+        assert e2 < TOL_BF16
+        g2.close()
     wt, v = g.params(), g.momentum()
     assert np.array_equal(g.replica(0), wt) and np.array_equal(g.replica(w.P - 1), wt)      # rebroadcast
     # first round from v = 0: w~_2 = w~_1 + v_2 holds to one fp32 rounding
@@ -256,10 +278,10 @@ def test_large_leaves_the_oracle_no_faster_than_a_cpu_fp32_twin(monkeypatch):
     worst_gpu = worst_twin = 0.0
     for k in range(steps):
         g.local_steps()                                   # K = 1 and no meta step: step k of the round
-        o.local_steps(learners=learners, workers=2)
+        _oracle_local_steps(o, learners)
         with monkeypatch.context() as m:
             m.setattr(O, "minibatch_gradient", _fp32_twin_gradient)
-            twin.local_steps(learners=learners, workers=2)
+            _oracle_local_steps(twin, learners)
         for j in learners:
             eg = replica_error(g.replica(j), o.replica(j), w.dims)
             et = replica_error(twin.replica(j), o.replica(j), w.dims)

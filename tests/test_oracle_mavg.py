@@ -440,3 +440,46 @@ def test_learners_walked_by_threads_give_the_same_run():
         runs.append((o.params(), o.momentum(), o.losses(), o.indices(), o.grad_sum))
     for a, b in zip(*runs):
         assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------------ local steps as low-rank terms
+def test_local_steps_are_rank_B_terms_on_top_of_the_round_start_weights():
+    """Algorithm 1: a learner's k-th local step subtracts lr * dZ_k^T A_k (a rank-B matrix) from each
+    weight matrix.  So along the oracle's own trajectory  W_k = W_0 - lr sum_{i<k} dZ_i^T A_i, and a
+    product with W_k can be formed without W_k:  A W_k^T = A W_0^T - lr sum_{i<k} (A A_i^T) dZ_i  and
+    dZ W_k = dZ W_0 - lr sum_{i<k} (dZ dZ_i^T) A_i.  Checked layer by layer against the replica the
+    oracle has actually stepped (the GPU's deferred-update mode relies on exactly this)."""
+    P, K, B, lr = 1, 4, 5, 0.1
+    X, y, w0 = _problem(DIMS, 60, 31)
+    o = O.MAvgOracle(P, 1, lr, 0.0, DIMS, B, index_seed=7)
+    o.set_params(w0)
+    o.set_data(X, y)
+    W0, b0 = O.unpack(w0.copy(), DIMS)
+    hist = []                                       # per step: (inputs of every layer, dZ of every layer)
+    rng = np.random.default_rng(0)
+    for k in range(K):
+        Wk, bk = O.unpack(o.replica(0), DIMS)       # the oracle's current weights
+        ib = O.minibatch_indices(7, 0, k, B, 60)
+        Zs, As = O.forward(Wk, bk, X[ib])
+        for l in range(len(Wk)):
+            # the stepped weights are the round-start ones plus the pending rank-B terms
+            want = W0[l] - lr * sum((dZ[l].T @ A[l] for A, dZ in hist), np.zeros_like(W0[l]))
+            assert np.max(np.abs(Wk[l] - want)) < 1e-14
+            # forward product without W_k
+            low_rank = As[l] @ W0[l].T - lr * sum(((As[l] @ A[l].T) @ dZ[l] for A, dZ in hist), 0.0)
+            assert np.max(np.abs(As[l] @ Wk[l].T - low_rank)) < 1e-12
+            # data-gradient product without W_k
+            g = rng.standard_normal((B, DIMS[l + 1]))
+            low_rank = g @ W0[l] - lr * sum(((g @ dZ[l].T) @ A[l] for A, dZ in hist), 0.0)
+            assert np.max(np.abs(g @ Wk[l] - low_rank)) < 1e-12
+        # this step's dZ_l, recomputed from the definition (the oracle's backward pass keeps none)
+        _, dZL = O.softmax_cross_entropy(Zs[-1], y[ib])
+        dZs = [None] * len(Wk)
+        dZ = dZL
+        for l in range(len(Wk) - 1, -1, -1):
+            dZs[l] = dZ
+            if l > 0:
+                dZ = (dZ @ Wk[l]) * (Zs[l - 1] > 0)
+        hist.append((As, dZs))
+        o.local_steps()                             # K = 1 per call: one more local step, no meta step
+    assert len(hist) == K and np.max(np.abs(o.replica(0) - w0)) > 1e-3
