@@ -12,8 +12,14 @@ the fused meta step (kavg_meta_update).  Prints ONE JSON line:
               library's stream, recorded inside the timed region)
   cpu_baseline  the CPU oracle, as it stands, on a bounded sample of the same
               workload (reported for context, not a target)
+  other_workloads  the remaining training workloads, same measurements, and
+              noisy_wide once more with deferred weight updates
   meta_update the fused meta step alone on the meta-only workload
               (P=64 replicas of an 11.2M-parameter fp32 vector), GB/s vs HBM peak
+  ceilings    what this device streams (read, write, 1:1) and multiplies (bf16
+              MFMA chain) with nothing else to do, from the library's probe kernels
+
+The headline workload is `large`, the largest single-GPU configuration.
 """
 import argparse
 import hashlib
@@ -95,7 +101,7 @@ def stored_traffic(workload, kernel_class):
     return rec.get("traffic_bytes_per_launch", {}).get(workload, {}).get(kernel_class)
 
 
-def cpu_baseline(w, data, beta=0.0, target_flops=1.0e12):
+def cpu_baseline(w, data, beta=0.0, target_flops=3.0e12):
     """The oracle, as it stands, on whole meta rounds of this workload restricted to its first
     learners (learners are independent between meta steps, so the rate per learner-sample is that
     of the full workload).  The sample is sized to about target_flops of arithmetic (some tens of
