@@ -91,7 +91,9 @@ __device__ __forceinline__ float wave_sum(float x) {
     return x;
 }
 
-template <bool BF16>
+// NPL > 0: C <= 64*NPL, the row is read once and stays in NPL registers per lane (logit c = lane + 64*i);
+// NPL == 0: any C, the row is read once per pass.
+template <bool BF16, int NPL>
 __global__ void __launch_bounds__(256)
 softmax_ce_kernel(const float* __restrict__ logits, int ldz, int C, const int32_t* __restrict__ y,
                   const int32_t* __restrict__ idx, long idx_learner_stride, int B, int P,
@@ -104,26 +106,48 @@ softmax_ce_kernel(const float* __restrict__ logits, int ldz, int C, const int32_
     label = label < 0 ? 0 : (label >= C ? C - 1 : label); // labels were validated; never index outside
     const float* z = logits + row * ldz;
     const long dz_row = (long)j * dz_learner_stride + (long)m * ldz;
-
-    float mx = -INFINITY;
-    for (int c = lane; c < C; c += 64) mx = fmaxf(mx, z[c]);
-    mx = wave_max(mx);
-    float sum = 0.f;
-    for (int c = lane; c < C; c += 64) sum += expf(z[c] - mx);
-    sum = wave_sum(sum);
     const float invB = 1.0f / (float)B;
-    for (int c = lane; c < ldz; c += 64) {
-        float g = 0.f;
-        if (c < C) {
-            float p = expf(z[c] - mx) / sum;
-            g = (p - (c == label ? 1.0f : 0.0f)) * invB;
-        }
+    auto store = [&](int c, float g) {
         if (BF16) {
             __bf16 h = (__bf16)g;
             ((uint16_t*)dz)[dz_row + c] = __builtin_bit_cast(uint16_t, h);
         } else {
             ((float*)dz)[dz_row + c] = g;
         }
+    };
+    if constexpr (NPL > 0) {
+        float zr[NPL];
+#pragma unroll
+        for (int i = 0; i < NPL; ++i) { const int c = lane + 64 * i; zr[i] = c < C ? z[c] : -INFINITY; }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < NPL; ++i) mx = fmaxf(mx, zr[i]);
+        mx = wave_max(mx);
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < NPL; ++i) { zr[i] = lane + 64 * i < C ? expf(zr[i] - mx) : 0.f; sum += zr[i]; }
+        sum = wave_sum(sum);
+#pragma unroll
+        for (int i = 0; i < NPL; ++i) {
+            const int c = lane + 64 * i;
+            if (c < ldz) store(c, c < C ? (zr[i] / sum - (c == label ? 1.0f : 0.0f)) * invB : 0.f);
+        }
+        if (lane == 0) rowloss[row] = -(z[label] - mx - logf(sum));
+        return;
+    }
+    float mx = -INFINITY;
+    for (int c = lane; c < C; c += 64) mx = fmaxf(mx, z[c]);
+    mx = wave_max(mx);
+    float sum = 0.f;
+    for (int c = lane; c < C; c += 64) sum += expf(z[c] - mx);
+    sum = wave_sum(sum);
+    for (int c = lane; c < ldz; c += 64) {
+        float g = 0.f;
+        if (c < C) {
+            float p = expf(z[c] - mx) / sum;
+            g = (p - (c == label ? 1.0f : 0.0f)) * invB;
+        }
+        store(c, g);
     }
     if (lane == 0) rowloss[row] = -(z[label] - mx - logf(sum));
 }
@@ -133,12 +157,16 @@ hipError_t launch_softmax_ce(const float* logits, int ldz, int C, const int32_t*
                              void* dz, long dz_learner_stride, int dz_bf16, float* rowloss, hipStream_t st) {
     long rows = (long)P * B;
     unsigned grid = (unsigned)((rows + 3) / 4);
-    if (dz_bf16)
-        hipLaunchKernelGGL(softmax_ce_kernel<true>, dim3(grid), dim3(256), 0, st, logits, ldz, C, y,
-                           idx, idx_learner_stride, B, P, dz, dz_learner_stride, rowloss);
-    else
-        hipLaunchKernelGGL(softmax_ce_kernel<false>, dim3(grid), dim3(256), 0, st, logits, ldz, C, y,
-                           idx, idx_learner_stride, B, P, dz, dz_learner_stride, rowloss);
+#define KAVG_SOFTMAX(BF, NPL)                                                                             \
+    hipLaunchKernelGGL((softmax_ce_kernel<BF, NPL>), dim3(grid), dim3(256), 0, st, logits, ldz, C, y, idx,  \
+                       idx_learner_stride, B, P, dz, dz_learner_stride, rowloss)
+    const int per_lane = (ldz + 63) / 64;
+    if (dz_bf16) {
+        if (per_lane <= 2) KAVG_SOFTMAX(true, 2); else if (per_lane <= 16) KAVG_SOFTMAX(true, 16); else KAVG_SOFTMAX(true, 0);
+    } else {
+        if (per_lane <= 2) KAVG_SOFTMAX(false, 2); else if (per_lane <= 16) KAVG_SOFTMAX(false, 16); else KAVG_SOFTMAX(false, 0);
+    }
+#undef KAVG_SOFTMAX
     return hipGetLastError();
 }
 
