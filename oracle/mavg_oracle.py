@@ -195,13 +195,18 @@ def meta_step(w_tilde, v, replicas, mu):
 class MAvgOracle:
     """State machine with the same call names as the C library."""
 
-    def __init__(self, P, K, lr, mu, dims, B, bf16=False, index_seed=0, learner_momentum=0.0):
+    def __init__(self, P, K, lr, mu, dims, B, bf16=False, index_seed=0, learner_momentum=0.0,
+                 gradient=None, n_params=None):
+        """gradient / n_params: another instance of the objective F(w) of Section 2 than the MLP
+        (a function (w, Xb, yb, bf16) -> (mean loss, flat gradient) and its parameter count);
+        Algorithm 1 itself does not depend on the model."""
         assert P >= 1 and K >= 1 and B >= 1 and lr >= 0.0 and 0.0 <= mu < 1.0
         assert 0.0 <= learner_momentum < 1.0
         self.beta = float(learner_momentum)
         self.P, self.K, self.lr, self.mu = P, K, float(lr), float(mu)
         self.dims, self.B, self.bf16, self.seed = tuple(dims), B, bool(bf16), int(index_seed)
-        self.n = num_params(self.dims)
+        self.gradient = gradient
+        self.n = num_params(self.dims) if n_params is None else int(n_params)
         self.w_tilde = None
         self.v = None
         self.reps = None
@@ -233,7 +238,7 @@ class MAvgOracle:
     def set_data(self, X, y):
         self.X = np.asarray(X)
         self.y = np.asarray(y)
-        assert self.X.shape[1] == self.dims[0]
+        assert self.gradient is not None or self.X.shape[1] == self.dims[0]
 
     def set_indices(self, idx):
         """idx [P][K][B] to use in every following local_steps call, or None
@@ -257,7 +262,10 @@ class MAvgOracle:
             idx[k] = ib
             Xb = self.X[ib].astype(np.float64)
             yb = self.y[ib]
-            loss, g = minibatch_gradient(w, self.dims, Xb, yb, self.bf16)
+            if self.gradient is not None:
+                loss, g = self.gradient(w, Xb, yb, self.bf16)
+            else:
+                loss, g = minibatch_gradient(w, self.dims, Xb, yb, self.bf16)
             losses[k] = loss
             gsum += g
             if self.beta > 0.0:
