@@ -12,8 +12,9 @@ the fused meta step (kavg_meta_update).  Prints ONE JSON line:
               library's stream, recorded inside the timed region)
   cpu_baseline  the CPU oracle, as it stands, on a bounded sample of the same
               workload (reported for context, not a target)
-  other_workloads  the remaining training workloads, same measurements, and
-              noisy_wide once more with deferred weight updates
+  other_workloads  the remaining training workloads, same measurements,
+              noisy_wide once more with deferred weight updates, and the
+              convolutional workload (times per kernel class, flops against the MFMA peak)
   meta_update the fused meta step alone on the meta-only workload
               (P=64 replicas of an 11.2M-parameter fp32 vector), GB/s vs HBM peak
   ceilings    what this device streams (read, write, 1:1) and multiplies (bf16
@@ -34,8 +35,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 from paper_2110_00625_amd import kavg, synth                                   # noqa: E402
-from paper_2110_00625_amd.configs import (WORKLOADS, META_ONLY, flops_per_learner_step,  # noqa: E402
-                                          num_params)
+from paper_2110_00625_amd.configs import (WORKLOADS, CONV_WORKLOADS, META_ONLY, flops_per_learner_step,  # noqa: E402
+                                          conv_flops_per_learner_step, num_params)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
@@ -301,12 +302,53 @@ def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration
     return res, data
 
 
+def run_conv_workload(torch, w, steps, warmup):
+    """The convolutional workload: `warmup` rounds with every kernel class bracketed, then `steps`
+    timed rounds without events."""
+    data = synth.make_conv_workload_inputs(w)
+    g = kavg.MAvg(w.P, w.K, w.lr, w.mu, w.dims, w.B, kavg.KAVG_BF16, index_seed=w.seeds["index"],
+                  conv=(w.H, w.W, w.channels))
+    X = torch.from_numpy(data["Xbits"].view(np.int16).reshape(w.N, w.H, w.W, w.channels[0])).cuda()
+    g.set_data(X, torch.from_numpy(data["y"]).cuda())
+    g.set_params(data["w0"])
+    classes = ["index", "forward", "loss", "backward", "update", "meta", "head"]
+    g.profile(classes)
+    for _ in range(max(warmup, 1)):
+        g.local_steps()
+        g.meta_update()
+    breakdown = g.profile_read()
+    g.profile([])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        g.local_steps()
+        g.meta_update()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    loss_first, loss_last = float(g.losses()[0].mean()), float(g.losses()[-1].mean())
+    g.close()
+    del X
+    torch.cuda.empty_cache()
+    flops = conv_flops_per_learner_step(w.H, w.W, w.channels, w.dims, w.B) * w.P * w.K
+    return {
+        "value": w.P * w.K * w.B * steps / dt, "ms_per_step": 1e3 * dt / steps, "steps": steps, "dtype": "bf16",
+        "config": {"workload": "%s: P=%d K=%d B=%d mu=%g lr=%g, %dx%d images, 3x3 convolutions %s, mean over positions, "
+                               "MLP %s, N=%d" % (w.name, w.P, w.K, w.B, w.mu, w.lr, w.H, w.W, "-".join(map(str, w.channels)),
+                                                 "-".join(map(str, w.dims)), w.N),
+                   "samples_per_step": w.P * w.K * w.B, "flops_per_step": flops},
+        "flops_fraction_of_bf16_mfma_peak": flops / (dt / steps) / (MFMA_BF16_PEAK_TFLOPS * 1e12),
+        "achieved_TFLOPs": flops / (dt / steps) / 1e12,
+        "kernel_classes": {c: {"ms_per_round": breakdown[c][0] / max(warmup, 1)} for c in classes},
+        "final_mean_loss": loss_last,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="large", choices=[k for k, v in WORKLOADS.items() if v.dims],
+    ap.add_argument("--workload", default="large", choices=[k for k, v in WORKLOADS.items() if v.dims] + list(CONV_WORKLOADS),
                     help="the headline workload (default: the largest single-GPU configuration)")
     ap.add_argument("--also", default="noisy_wide,cifar_mlp,tiny",
                     help="comma-separated further workloads reported under other_workloads ('' = none)")
@@ -315,6 +357,8 @@ def main():
                          "updates; 1 = every step, the default)")
     ap.add_argument("--also-deferred", default="noisy_wide:16",
                     help="workload:m pairs also run with deferred updates and reported under other_workloads ('' = none)")
+    ap.add_argument("--also-conv", default="cifar_conv",
+                    help="convolutional workloads reported under other_workloads ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-meta-only", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true")
@@ -333,6 +377,21 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     kavg.load_library()
+    if args.workload in CONV_WORKLOADS:
+        # the convolutional workload as the line's subject: its dense products are bound by the matrix cores
+        r = run_conv_workload(torch, CONV_WORKLOADS[args.workload], args.steps, args.warmup)
+        dense_ms = sum(r["kernel_classes"][c]["ms_per_round"] for c in ("forward", "backward", "update"))
+        ach = r["config"]["flops_per_step"] / (dense_ms * 1e-3) / 1e12
+        out = {"metric": "learner-samples/sec (all P on 1 GPU); meta-update GB/s vs HBM peak",
+               "value": r["value"], "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+               "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+               "dtype": "bf16", "data": "synthetic", "config": r["config"],
+               "roofline": {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                            "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                            "kernel_class": "forward+backward+update of the bracketed warm-up rounds"},
+               "kernel_classes": r["kernel_classes"], "final_mean_loss": r["final_mean_loss"]}
+        print(json.dumps(out))
+        return
     w = WORKLOADS[args.workload]
     res, data = run_workload(torch, w, args.steps, args.warmup, args.learner_momentum, args.copy_calibration,
                              refresh=args.refresh)
@@ -361,6 +420,8 @@ def main():
             "config": r["config"],
             "flops_fraction_of_bf16_mfma_peak": r["config"]["flops_per_step"] / (r["ms_per_step"] * 1e-3) / (MFMA_BF16_PEAK_TFLOPS * 1e12),
             "kernel_classes": {k: {"ms_per_round": v["ms_per_round"]} for k, v in r["kernel_classes"].items()}}
+    for name in [x for x in args.also_conv.split(",") if x]:
+        others[name] = run_conv_workload(torch, CONV_WORKLOADS[name], min(args.steps, 10), min(args.warmup, 2))
     if others:
         out["other_workloads"] = others
     if not args.no_meta_only:

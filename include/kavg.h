@@ -90,6 +90,27 @@ int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu,
               int n_layers, const int* dims, int B, int dtype, uint64_t index_seed,
               void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
+/* The learner of Section 4's convolutional workloads (the paper trains CNNs on image sets): F is a
+ * stack of n_conv 3x3 convolutions (stride 1, zero padding 1, each followed by ReLU) on H x W
+ * channels-last images, the mean over the H*W positions, and then the MLP dims[0..n_layers] with
+ * dims[0] == channels[n_conv]; everything else (Algorithm 1's local steps, averaging, block
+ * momentum, index stream) is kavg_init's.  KAVG_BF16 arithmetic only.
+ * channels[0..n_conv]: input channels, then each convolution's output channels, all multiples of 8
+ * (pad the input images with zero channels).  The flat parameter vector holds, per convolution,
+ * W [c_out][3][3][c_in] (row-major; tap (kh,kw) reads input pixel (h+kh-1, w+kw-1)) and then its bias
+ * [c_out]; the MLP's layers follow in kavg_init's order.  kavg_set_data takes X [N][H][W][channels[0]]
+ * bf16.  kavg_set_learner_momentum and kavg_set_refresh are refused on such a context.
+ * kavg_num_params_conv / kavg_workspace_bytes_conv: length of the flat vector / bytes of workspace,
+ * 0 for a configuration kavg_init_conv would refuse.
+ * Errors: as kavg_init, plus KAVG_EINVAL for H or W outside [1,4096], n_conv outside [1,63], a
+ * channel count that is not a multiple of 8 in [8,4096], B*H*W >= 2^30, dims[0] != channels[n_conv]. */
+size_t kavg_num_params_conv(int H, int W, int n_conv, const int* channels, int n_layers, const int* dims);
+size_t kavg_workspace_bytes_conv(int P, int K, int B, int H, int W, int n_conv, const int* channels,
+                                 int n_layers, const int* dims);
+int kavg_init_conv(kavg_ctx** out, int P, int K, float lr, float mu, int H, int W, int n_conv,
+                   const int* channels, int n_layers, const int* dims, int B, uint64_t index_seed,
+                   void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
 /* kavg_init for callers that cannot allocate device memory (code running under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc): the context works in a block of
  * KAVG_STATIC_WORKSPACE_BYTES that lives inside the library's device image (one copy per GPU, held

@@ -1,5 +1,5 @@
-"""Workload table: the five synthetic configurations the M-AVG hot path is
-checked and measured on.
+"""Workload table: the synthetic configurations the M-AVG hot path is
+checked and measured on (five MLP / flat-vector ones and a convolutional one).
 
 Each entry fixes the hyper-parameters of Algorithm 1 (P learners, K local
 steps, batch B, step size lr, block momentum mu, number of meta rounds), the
@@ -33,6 +33,12 @@ class Workload:
     label_flip: float = 0.0  # fraction of labels replaced by a different class
     flat_n: int = 0         # meta-only workload: length of the flat vector
     seeds: dict = field(default_factory=dict)
+    # convolutional workload: 3x3 convolutions on H x W images in front of the MLP
+    # (channels[0] = input channels padded to a multiple of 8, of which c_real carry data)
+    H: int = 0
+    W: int = 0
+    channels: Tuple[int, ...] = ()
+    c_real: int = 0
 
     @property
     def n_classes(self) -> int:
@@ -63,7 +69,32 @@ LARGE = Workload("large", P=8, K=32, B=256, mu=0.95, lr=0.2, rounds=10,
                  dims=(3072, 4096, 4096, 1000), dtype=DTYPE_BF16, N=200000,
                  seeds=_seeds(5))
 
+# CIFAR-shaped images (32x32x3, Section 4) through three 3x3 convolutions, the mean over the
+# positions and a small MLP
+CIFAR_CONV = Workload("cifar_conv", P=16, K=8, B=64, mu=0.9, lr=0.05, rounds=20,
+                      dims=(128, 256, 10), dtype=DTYPE_BF16, N=10000, seeds=_seeds(6),
+                      H=32, W=32, channels=(8, 32, 64, 128), c_real=3)
+
 WORKLOADS = {w.name: w for w in (TINY, CIFAR_MLP, NOISY_WIDE, META_ONLY, LARGE)}
+CONV_WORKLOADS = {w.name: w for w in (CIFAR_CONV,)}
+
+
+def conv_num_params(channels, dims) -> int:
+    """Flat length of a convolutional net: per convolution W [c_out][3][3][c_in] and bias, then the MLP."""
+    return sum(channels[t] * 9 * channels[t - 1] + channels[t] for t in range(1, len(channels))) + num_params(dims)
+
+
+def conv_flops_per_learner_step(H, W, channels, dims, B) -> int:
+    """Dense-product flops of one learner step: per convolution forward, weight gradient and (from the
+    second one on) data gradient, 2 flops per weight and position each; the MLP with a data gradient
+    in every layer (its first layer hands the gradient of the pooled vector on)."""
+    rows = B * H * W
+    tot = 0
+    for t in range(1, len(channels)):
+        tot += (6 if t > 1 else 4) * rows * 9 * channels[t - 1] * channels[t]
+    for l in range(1, len(dims)):
+        tot += 6 * B * dims[l] * dims[l - 1]
+    return tot
 
 
 def num_params(dims) -> int:

@@ -93,6 +93,9 @@ struct Args {
     int epi; float alpha;
     const float* base; size_t base_lstride; int ld_base;
     int skip_bias;
+    //                  partial != null: store the fp32 accumulators (and column sums of R) instead of stepping
+    //                  the master; "learners" are then ranges of rows of the real learners
+    float* partial; float* partial_bias;
 };
 enum { EPI_STD = 0, EPI_GRAM = 1, EPI_RAW = 2, EPI_RELU = 3, EPI_LOGITS = 4 };
 
@@ -523,8 +526,11 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
             // without predicates (rows and columns beyond the layer are clamped; those lanes store
             // nothing later), so that the compiler can count them: the wait for the operand slice is
             // then "all but these", not "everything".
-            const uint16_t* hbase = a.ws + (size_t)learner * a.ws_lstride;
-            const uint16_t* lbase = a.wlo + (size_t)learner * a.ws_lstride;
+            // (with partial outputs nothing is stepped; the loads then go to learner 0's tile and are ignored,
+            // so that the load sequence keeps its branch-free shape)
+            const size_t mlearner = a.partial ? 0 : (size_t)learner;
+            const uint16_t* hbase = a.ws + mlearner * a.ws_lstride;
+            const uint16_t* lbase = a.wlo + mlearner * a.ws_lstride;
             const int c = min(c0 + wc * WTC + (lane % L8_PER_ROW) * 8, a.nC - 8);
 #pragma unroll
             for (int i = 0; i < MR; ++i)
@@ -684,6 +690,14 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                 const int r = rblk + it * ROWS_PER_IT + rr;
                 const float* gp = stage + (it * ROWS_PER_IT + rr) * SPITCH + cc;
                 const f32x4 g0 = *(const f32x4*)gp, g1 = *(const f32x4*)(gp + 4);
+                if (a.partial) {
+                    if (r < a.nR && c < a.nC) {
+                        float* pp = a.partial + ((size_t)learner * a.nR + r) * a.nC + c;
+                        *(f32x4*)pp = g0;
+                        *(f32x4*)(pp + 4) = g1;
+                    }
+                    continue;
+                }
                 if (r < a.nR && c < a.nC) {
                     float step[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
                     if (a.u) {                                  // heavy ball inside the learner
@@ -715,7 +729,9 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
                 }
             }
         }
-        if (!a.skip_bias && tile_c == 0 && tid < TR && r0 + tid < a.nR) {
+        if (a.partial) {
+            if (tile_c == 0 && tid < TR && r0 + tid < a.nR) a.partial_bias[(size_t)learner * a.nR + r0 + tid] = bias_sum;
+        } else if (!a.skip_bias && tile_c == 0 && tid < TR && r0 + tid < a.nR) {
             const size_t at = (size_t)learner * a.w_lstride + r0 + tid;
             if (a.ub) { bias_sum = a.beta * a.ub[at] + bias_sum; a.ub[at] = bias_sum; }
             const size_t sat = (size_t)learner * a.ws_lstride + r0 + tid;
@@ -758,6 +774,8 @@ enum { T128x128 = 0, T128x64 = 1, T64x128 = 2, T64x64_K2 = 3 };
 // groups (most wavefronts per compute unit, half as many barriers per k) wins.
 int pick_tile(int mode, int nR, int nC, int P) {
     const long tiles128 = (long)((nR + 127) / 128) * ((nC + 127) / 128) * P;
+    // few output columns (convolution channels): a 64-column tile wastes least
+    if (nC <= 64 && nR > 64 && tiles128 >= 512) return T128x64;
     if (mode == MODE_FWD) {
         if (nR <= 64) return (long)((nC + 127) / 128) * P >= 512 ? T64x128 : T64x64_K2;
         return tiles128 >= 512 ? T128x128 : T64x64_K2;
@@ -813,9 +831,18 @@ hipError_t bf16_backward_data(const LayerCall& c, hipStream_t st) {
 
 hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     Args a = {};
-    const int rows = c.rows ? c.rows : c.B;
-    a.R = {(const uint16_t*)c.dz, c.dz_stride, c.ld_dz, nullptr, 0, rows, c.ld_dz};         // memory row = k: R(r, k) = dZ[k][r]
-    a.C = {(const uint16_t*)c.in, c.gather ? 0 : c.in_stride, c.ld_in, c.gather, c.gather_stride, rows, c.d_in};
+    int rows = c.rows ? c.rows : c.B;
+    int P = c.P;
+    size_t r_stride = c.dz_stride, c_stride = c.gather ? 0 : c.in_stride;
+    if (c.partial) {                               // ranges of rows as separate "learners" (rows are contiguous per learner)
+        if (c.gather || c.splits < 1 || rows % c.splits != 0 || c.dz_stride != (size_t)rows * c.ld_dz ||
+            c.in_stride != (size_t)rows * c.ld_in) return hipErrorInvalidValue;
+        rows /= c.splits; P *= c.splits;
+        r_stride = (size_t)rows * c.ld_dz; c_stride = (size_t)rows * c.ld_in;
+        a.partial = c.partial; a.partial_bias = c.partial_bias;
+    }
+    a.R = {(const uint16_t*)c.dz, r_stride, c.ld_dz, nullptr, 0, rows, c.ld_dz};         // memory row = k: R(r, k) = dZ[k][r]
+    a.C = {(const uint16_t*)c.in, c_stride, c.ld_in, c.gather, c.gather_stride, rows, c.d_in};
     a.nR = c.d_out; a.nC = c.d_in; a.nK = rows;
     a.skip_bias = c.skip_bias;
     a.ws = c.ws; a.wlo = c.wlo; a.ws_lstride = c.ws_stride; a.bhi = c.bhi; a.blo = c.blo; a.w_lstride = c.w_stride;
@@ -825,18 +852,18 @@ hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     // (128-byte row segments per plane), as 128x64 where the bf16 planes stay in the memory-side
     // cache (CIFAR-MLP) and as 64x128 where they stream (the 4096-wide workloads with batches up to 128).
     if (c.shadow_cached) {
-        if (c.gather) return launch<MODE_UPD, 128, 64, 4, 1, 1, 64, true, true, PIPE_PLAIN, true, true>(a, c.P, st);
-        return launch<MODE_UPD, 128, 64, 4, 1, 1, 64, true, true, PIPE_PLAIN, true, false>(a, c.P, st);
+        if (c.gather) return launch<MODE_UPD, 128, 64, 4, 1, 1, 64, true, true, PIPE_PLAIN, true, true>(a, P, st);
+        return launch<MODE_UPD, 128, 64, 4, 1, 1, 64, true, true, PIPE_PLAIN, true, false>(a, P, st);
     }
     if (rows > 128) {
         // Long contractions: per output tile the two operands (read out of the L2 cache, B rows each) weigh as
         // much as the master tile itself, and a compute unit can only pull so many bytes per clock; a
         // 128x128 tile reads a third less of them per weight (large: 15.0 -> 14.5 ms per round).
-        if (c.gather) return launch<MODE_UPD, 128, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, true>(a, c.P, st);
-        return launch<MODE_UPD, 128, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, false>(a, c.P, st);
+        if (c.gather) return launch<MODE_UPD, 128, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, true>(a, P, st);
+        return launch<MODE_UPD, 128, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, false>(a, P, st);
     }
-    if (c.gather) return launch<MODE_UPD, 64, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, true>(a, c.P, st);
-    return launch<MODE_UPD, 64, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, false>(a, c.P, st);
+    if (c.gather) return launch<MODE_UPD, 64, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, true>(a, P, st);
+    return launch<MODE_UPD, 64, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, false>(a, P, st);
 }
 
 hipError_t bf16_gram(const GramCall& c, hipStream_t st) {

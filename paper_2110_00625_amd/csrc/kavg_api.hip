@@ -28,8 +28,24 @@ struct Layout {
     size_t off_logits = 0, off_rowloss = 0, off_losses = 0, off_scratch = 0;
     std::vector<size_t> off_act, off_dz;   // per layer l = 1..L (index l-1); act of the last layer unused
     std::vector<size_t> w_off, b_off;      // parameter offsets inside a replica
+    // convolution stack in front of the MLP (kavg_init_conv); empty for a plain MLP
+    std::vector<size_t> cw_off, cb_off;    // parameter offsets of the convolutions (they come first in the flat vector)
+    std::vector<size_t> off_patch, off_cact, off_cdz;   // per convolution: patch matrix, output images, their dZ
+    std::vector<int> splits;               // ranges of positions its weight gradient is split over
+    size_t off_draw = 0, off_pool = 0, off_dpool = 0, off_partial = 0, off_pbias = 0;
     size_t total = 0;
 };
+
+// H x W images, channels ch[0] (input) .. ch[M]; ch empty: plain MLP
+struct ConvSpec { int H = 0, W = 0; std::vector<int> ch; };
+
+bool conv_ok(const ConvSpec& cv, int L, const int* dims, int dtype, int B) {
+    if (cv.ch.empty()) return true;
+    if (dtype != KAVG_BF16 || cv.H < 1 || cv.W < 1 || cv.H > 4096 || cv.W > 4096 || cv.ch.size() < 2 || cv.ch.size() > 64) return false;
+    for (int c : cv.ch) if (c < 8 || c % 8 != 0 || c > 4096) return false;
+    if ((size_t)B * cv.H * cv.W >= ((size_t)1 << 30)) return false;
+    return dims[0] == cv.ch.back();
+}
 
 bool shapes_ok(int P, int K, int B, int L, const int* dims, int dtype) {
     if (P < 1 || K < 1 || B < 1 || L < 1 || !dims) return false;
@@ -42,10 +58,17 @@ bool shapes_ok(int P, int K, int B, int L, const int* dims, int dtype) {
     return true;
 }
 
-Layout make_layout(int P, int K, int B, int L, const int* dims, int dtype) {
+Layout make_layout(int P, int K, int B, int L, const int* dims, int dtype, const ConvSpec& cv = ConvSpec()) {
     Layout lo;
     const size_t esz = dtype == KAVG_BF16 ? 2 : 4;     // activation / dZ element size
     size_t o = 0;
+    const int M = cv.ch.empty() ? 0 : (int)cv.ch.size() - 1;
+    for (int t = 1; t <= M; ++t) {
+        lo.cw_off.push_back(o);
+        o += (size_t)cv.ch[t] * 9 * cv.ch[t - 1];
+        lo.cb_off.push_back(o);
+        o += cv.ch[t];
+    }
     for (int l = 1; l <= L; ++l) {
         lo.w_off.push_back(o);
         o += (size_t)dims[l] * dims[l - 1];
@@ -81,6 +104,30 @@ Layout make_layout(int P, int K, int B, int L, const int* dims, int dtype) {
             if (splits > 1 && (size_t)splits * P * B * ld * 4 > need) need = (size_t)splits * P * B * ld * 4;
         }
         lo.off_scratch = need ? take(need) : 0;
+    }
+    if (M > 0) {
+        const size_t rows = (size_t)B * cv.H * cv.W;
+        size_t draw = 0, partial = 0, pbias = 0;
+        for (int t = 1; t <= M; ++t) {
+            lo.off_patch.push_back(take((size_t)P * rows * 9 * cv.ch[t - 1] * 2));
+            lo.off_cact.push_back(take((size_t)P * rows * cv.ch[t] * 2));
+            lo.off_cdz.push_back(take((size_t)P * rows * cv.ch[t] * 2));
+            if (t > 1 && (size_t)P * rows * 9 * cv.ch[t - 1] * 4 > draw) draw = (size_t)P * rows * 9 * cv.ch[t - 1] * 4;
+            // split the weight gradient's contraction until the launch has some hundreds of workgroups,
+            // keeping at least 256 positions per range
+            const size_t tiles = (size_t)((cv.ch[t] + 127) / 128) * ((9 * cv.ch[t - 1] + 127) / 128) * P;
+            int S = 1;
+            while (tiles * S < 512 && rows % (2 * (size_t)S) == 0 && rows / (2 * (size_t)S) >= 256) S *= 2;
+            lo.splits.push_back(S);
+            const size_t nw = (size_t)cv.ch[t] * 9 * cv.ch[t - 1];
+            if ((size_t)P * S * nw * 4 > partial) partial = (size_t)P * S * nw * 4;
+            if ((size_t)P * S * cv.ch[t] * 4 > pbias) pbias = (size_t)P * S * cv.ch[t] * 4;
+        }
+        lo.off_draw = draw ? take(draw) : 0;
+        lo.off_pool = take((size_t)P * B * cv.ch[M] * 2);
+        lo.off_dpool = take((size_t)P * B * cv.ch[M] * 2);
+        lo.off_partial = take(partial);
+        lo.off_pbias = take(pbias);
     }
     lo.total = p;
     return lo;
@@ -146,6 +193,7 @@ struct kavg_ctx {
     bool graph_on = false;
     bool warm = false;                  // the sequence has run eagerly once with the current pointers
     hipGraphExec_t gexec = nullptr;
+    ConvSpec cv;                        // convolution stack in front of the MLP (empty: plain MLP)
     // deferred weight updates (kavg_set_refresh): history block, its carve-up, refresh period
     int refresh = 1;
     char* hist = nullptr;
@@ -261,7 +309,10 @@ LayerCall layer_call(const kavg_ctx* c, int l /*1..L*/, int k) {
         q.b = c->reps() + lo.b_off[l - 1];
     }
     q.shadow_cached = shadows_stay_cached(c->P, lo.stride);
-    if (l == 1) {
+    if (l == 1 && !c->cv.ch.empty()) {       // behind a convolution stack: the mean over the positions
+        q.in = c->ws + lo.off_pool; q.ld_in = c->dims[0]; q.in_stride = (size_t)c->B * q.ld_in;
+        q.dz_prev = c->ws + lo.off_dpool; q.dz_prev_stride = q.in_stride;
+    } else if (l == 1) {
         q.in = c->X; q.ld_in = c->dims[0]; q.in_stride = 0;
         q.gather = c->idx() + (size_t)k * c->B; q.gather_stride = (long)c->K * c->B;
         q.next_gather = k + 1 < c->K ? q.gather + c->B : nullptr;
@@ -305,9 +356,20 @@ size_t kavg_workspace_bytes(int P, int K, int B, int n_layers, const int* dims, 
     try { return make_layout(P, K, B, n_layers, dims, dtype).total; } catch (...) { return 0; }
 }
 
-int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, const int* dims, int B,
-              int dtype, uint64_t index_seed, void* workspace_dev, size_t workspace_bytes,
-              void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+bool conv_spec(ConvSpec* cv, int H, int W, int n_conv, const int* channels) {
+    if (n_conv < 1 || n_conv > 63 || !channels) return false;
+    cv->H = H; cv->W = W;
+    cv->ch.assign(channels, channels + n_conv + 1);
+    return true;
+}
+
+int init_common(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, const int* dims, int B,
+                int dtype, uint64_t index_seed, void* workspace_dev, size_t workspace_bytes,
+                void* hip_stream, const ConvSpec& cv) {
     if (!out) return fail(nullptr, KAVG_EINVAL, "out is null");
     *out = nullptr;
     kavg_ctx* c = nullptr;
@@ -315,15 +377,19 @@ int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, co
     if (!shapes_ok(P, K, B, n_layers, dims, dtype))
         return fail(nullptr, KAVG_EINVAL, "bad shape: need P,K,B >= 1 (P,K <= 2^24, B <= 65536), "
                     "dims >= 1 and, for bf16, d_0..d_{L-1} multiples of 8");
+    if (!conv_ok(cv, n_layers, dims, dtype, B))
+        return fail(nullptr, KAVG_EINVAL, "bad convolution stack: need bf16, H,W in [1,4096], channel counts that are "
+                    "multiples of 8 in [8,4096], B*H*W < 2^30 and d_0 equal to the last channel count");
     if (!(lr >= 0.f) || !std::isfinite(lr)) return fail(nullptr, KAVG_EINVAL, "lr must be finite and >= 0");
     if (!(mu >= 0.f && mu < 1.f)) return fail(nullptr, KAVG_EINVAL, "mu must lie in [0,1)");
     if (!workspace_dev || ((uintptr_t)workspace_dev % ALIGN) != 0)
         return fail(nullptr, KAVG_EINVAL, "workspace must be a non-null, 256-byte aligned device pointer");
-    Layout lo = make_layout(P, K, B, n_layers, dims, dtype);
+    Layout lo = make_layout(P, K, B, n_layers, dims, dtype, cv);
     if (workspace_bytes < lo.total)
         return fail(nullptr, KAVG_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, lo.total);
     c = new (std::nothrow) kavg_ctx();
     if (!c) return fail(nullptr, KAVG_ENOMEM, "host allocation failed");
+    c->cv = cv;
     c->P = P; c->K = K; c->B = B; c->L = n_layers; c->dtype = dtype;
     c->lr = lr; c->mu = mu; c->seed = index_seed;
     c->dims.assign(dims, dims + n_layers + 1);
@@ -348,6 +414,56 @@ int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, co
     return KAVG_OK;
     } catch (...) {
         delete c;
+        return fail(nullptr, KAVG_ENOMEM, "host allocation failed");
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, const int* dims, int B,
+              int dtype, uint64_t index_seed, void* workspace_dev, size_t workspace_bytes,
+              void* hip_stream) {
+    return init_common(out, P, K, lr, mu, n_layers, dims, B, dtype, index_seed, workspace_dev, workspace_bytes,
+                       hip_stream, ConvSpec());
+}
+
+size_t kavg_num_params_conv(int H, int W, int n_conv, const int* channels, int n_layers, const int* dims) {
+    (void)H; (void)W;
+    if (n_conv < 1 || !channels) return 0;
+    size_t n = kavg_num_params(n_layers, dims);
+    if (n == 0) return 0;
+    for (int t = 1; t <= n_conv; ++t) {
+        if (channels[t] < 1 || channels[t - 1] < 1) return 0;
+        n += (size_t)channels[t] * 9 * channels[t - 1] + channels[t];
+    }
+    return n;
+}
+
+size_t kavg_workspace_bytes_conv(int P, int K, int B, int H, int W, int n_conv, const int* channels, int n_layers,
+                                 const int* dims) {
+    try {
+        ConvSpec cv;
+        if (!conv_spec(&cv, H, W, n_conv, channels)) return 0;
+        if (!shapes_ok(P, K, B, n_layers, dims, KAVG_BF16) || !conv_ok(cv, n_layers, dims, KAVG_BF16, B)) return 0;
+        return make_layout(P, K, B, n_layers, dims, KAVG_BF16, cv).total;
+    } catch (...) { return 0; }
+}
+
+int kavg_init_conv(kavg_ctx** out, int P, int K, float lr, float mu, int H, int W, int n_conv, const int* channels,
+                   int n_layers, const int* dims, int B, uint64_t index_seed, void* workspace_dev,
+                   size_t workspace_bytes, void* hip_stream) {
+    try {
+        ConvSpec cv;
+        if (!conv_spec(&cv, H, W, n_conv, channels)) {
+            if (out) *out = nullptr;
+            return fail(nullptr, KAVG_EINVAL, "need 1..63 convolutions and their channel counts");
+        }
+        return init_common(out, P, K, lr, mu, n_layers, dims, B, KAVG_BF16, index_seed, workspace_dev, workspace_bytes,
+                           hip_stream, cv);
+    } catch (...) {
+        if (out) *out = nullptr;
         return fail(nullptr, KAVG_ENOMEM, "host allocation failed");
     }
 }
@@ -426,8 +542,10 @@ namespace {
 // All arguments are fixed between calls (workspace pointers, data pointers, shapes), which is what
 // lets kavg_local_steps replay this sequence as a graph.
 int issue_steps_deferred(kavg_ctx* c);
+int issue_steps_conv(kavg_ctx* c);
 
 int issue_steps(kavg_ctx* c) {
+    if (!c->cv.ch.empty()) return issue_steps_conv(c);
     if (c->refresh > 1) return issue_steps_deferred(c);
     hipStream_t st = c->stream;
     const bool bf = c->dtype == KAVG_BF16;
@@ -505,6 +623,108 @@ extern "C++" HistoryLayout history_layout(const kavg_ctx* c, int m) {
     h.s = take((size_t)c->P * c->B * h.ldS * 2);
     h.total = p;
     return h;
+}
+
+// The K local steps of a network whose MLP sits behind a stack of 3x3 convolutions (the CNN workloads
+// of Section 4): per step and convolution the patch matrix is written out, the three products of a
+// dense layer run on it with B*H*W rows, and the mean over the positions joins the two parts.
+int issue_steps_conv(kavg_ctx* c) {
+    hipStream_t st = c->stream;
+    const Layout& lo = c->lo;
+    const ConvSpec& cv = c->cv;
+    const int L = c->L, M = (int)cv.ch.size() - 1, P = c->P, B = c->B, H = cv.H, W = cv.W;
+    const int rows = B * H * W;
+    const bool head = head_supported(c->dims[L]);
+    auto conv_call = [&](int t) {
+        LayerCall q{};
+        const int cin = 9 * cv.ch[t - 1], cout = cv.ch[t];
+        q.P = P; q.B = rows; q.rows = rows; q.d_in = cin; q.d_out = cout;
+        q.w_stride = lo.stride; q.ws_stride = lo.stride;
+        q.ws = c->hi_planes() + lo.cw_off[t - 1];
+        q.wlo = c->lo_planes() + lo.cw_off[t - 1];
+        q.bhi = c->hi_planes() + lo.cb_off[t - 1];
+        q.blo = c->lo_planes() + lo.cb_off[t - 1];
+        q.shadow_cached = shadows_stay_cached(P, lo.stride);
+        q.in = c->ws + lo.off_patch[t - 1]; q.ld_in = cin; q.in_stride = (size_t)rows * cin;
+        q.out = c->ws + lo.off_cact[t - 1]; q.ld_out = cout; q.out_stride = (size_t)rows * cout;
+        q.relu = 1;
+        q.dz = c->ws + lo.off_cdz[t - 1]; q.ld_dz = cout; q.dz_stride = (size_t)rows * cout;
+        q.lr = c->lr;
+        return q;
+    };
+    for (int k = 0; k < c->K; ++k) {
+        const int32_t* idx_k = c->idx() + (size_t)k * B;
+        const long idx_ls = (long)c->K * B;
+        float* rowloss_k = c->rowloss() + (size_t)k * P * B;
+        for (int t = 1; t <= M; ++t) {                              // convolutions, forward
+            Bracket br(c, KAVG_CLASS_FORWARD);
+            if (t == 1)
+                KAVG_HIP(c, launch_im2col(c->X, 0, idx_k, idx_ls, c->ws + lo.off_patch[0], P, B, H, W, cv.ch[0], st));
+            else
+                KAVG_HIP(c, launch_im2col(c->ws + lo.off_cact[t - 2], (size_t)rows * cv.ch[t - 1], nullptr, 0,
+                                          c->ws + lo.off_patch[t - 1], P, B, H, W, cv.ch[t - 1], st));
+            KAVG_HIP(c, bf16_forward(conv_call(t), st));
+        }
+        {
+            Bracket br(c, KAVG_CLASS_FORWARD);
+            KAVG_HIP(c, launch_pool_forward(c->ws + lo.off_cact[M - 1], c->ws + lo.off_pool, P, B, H * W, cv.ch[M], st));
+        }
+        for (int l = 1; l <= (head ? L - 1 : L); ++l) {             // MLP, forward
+            Bracket br(c, KAVG_CLASS_FORWARD);
+            KAVG_HIP(c, bf16_forward(layer_call(c, l, k), st));
+        }
+        if (head) {
+            Bracket br(c, KAVG_CLASS_HEAD);
+            KAVG_HIP(c, head_forward_backward(layer_call(c, L, k), c->y, idx_k, idx_ls, rowloss_k, 1, st));
+        } else {
+            Bracket br(c, KAVG_CLASS_LOSS);
+            KAVG_HIP(c, launch_softmax_ce(c->logits(), lo.ldz, c->dims[L], c->y, idx_k, idx_ls, B, P,
+                                          c->ws + lo.off_dz[L - 1], (long)B * lo.ldz, 1, rowloss_k, st));
+        }
+        for (int l = L; l >= 1; --l) {                              // MLP, backward; layer 1 hands dL/d(pooled) on
+            LayerCall q = layer_call(c, l, k);
+            if (head && l == L) {
+                Bracket br(c, KAVG_CLASS_HEAD);
+                KAVG_HIP(c, head_update(q, idx_k, idx_ls, 1, st));
+                continue;
+            }
+            {
+                Bracket br(c, KAVG_CLASS_BACKWARD);
+                KAVG_HIP(c, bf16_backward_data(q, st));
+            }
+            Bracket br(c, KAVG_CLASS_UPDATE);
+            KAVG_HIP(c, bf16_update(q, st));
+        }
+        {
+            Bracket br(c, KAVG_CLASS_BACKWARD);
+            KAVG_HIP(c, launch_pool_backward(c->ws + lo.off_dpool, c->ws + lo.off_cact[M - 1], c->ws + lo.off_cdz[M - 1],
+                                             P, B, H * W, cv.ch[M], st));
+        }
+        for (int t = M; t >= 1; --t) {                              // convolutions, backward
+            LayerCall q = conv_call(t);
+            if (t > 1) {
+                Bracket br(c, KAVG_CLASS_BACKWARD);
+                LayerCall r = q;
+                r.bwd_raw = 1;
+                r.dz_prev = c->ws + lo.off_draw; r.dz_prev_stride = (size_t)rows * q.d_in;
+                KAVG_HIP(c, bf16_backward_data(r, st));
+                KAVG_HIP(c, launch_col2im_mask((const float*)(c->ws + lo.off_draw), c->ws + lo.off_cact[t - 2],
+                                               c->ws + lo.off_cdz[t - 2], P, B, H, W, cv.ch[t - 1], st));
+            }
+            Bracket br(c, KAVG_CLASS_UPDATE);
+            q.partial = (float*)(c->ws + lo.off_partial);
+            q.partial_bias = (float*)(c->ws + lo.off_pbias);
+            q.splits = lo.splits[t - 1];
+            KAVG_HIP(c, bf16_update(q, st));
+            KAVG_HIP(c, launch_conv_step((uint16_t*)q.ws, (uint16_t*)q.wlo, (uint16_t*)q.bhi, (uint16_t*)q.blo, lo.stride,
+                                         q.partial, q.partial_bias, P, q.splits, q.d_out * q.d_in, q.d_out, c->lr, st));
+        }
+    }
+    {
+        Bracket br(c, KAVG_CLASS_LOSS);
+        KAVG_HIP(c, launch_loss_mean(c->rowloss(), c->losses(), c->K * P, B, st));
+    }
+    return KAVG_OK;
 }
 
 int issue_steps_deferred(kavg_ctx* c) {
@@ -835,6 +1055,7 @@ int kavg_set_learner_momentum(kavg_ctx* c, float beta, void* velocity_dev, size_
         return KAVG_OK;
     }
     if (c->refresh > 1) return fail(c, KAVG_ESTATE, "deferred updates and learner-level momentum exclude each other");
+    if (!c->cv.ch.empty()) return fail(c, KAVG_EINVAL, "learner-level momentum is not built for convolutional contexts");
     if (((uintptr_t)velocity_dev % ALIGN) != 0) return fail(c, KAVG_EINVAL, "velocity buffer must be 256-byte aligned");
     if (bytes < kavg_velocity_bytes(c)) return fail(c, KAVG_ENOMEM, "velocity buffer has %zu bytes, %zu needed", bytes, kavg_velocity_bytes(c));
     KAVG_HIP(c, hipMemsetAsync(velocity_dev, 0, kavg_velocity_bytes(c), c->stream));
@@ -868,6 +1089,7 @@ int kavg_set_refresh(kavg_ctx* c, int refresh, void* history_dev, size_t bytes) 
         return KAVG_OK;
     }
     if (c->dtype != KAVG_BF16) return fail(c, KAVG_EINVAL, "deferred updates are built for KAVG_BF16 only");
+    if (!c->cv.ch.empty()) return fail(c, KAVG_EINVAL, "deferred updates are not built for convolutional contexts");
     if (c->vel) return fail(c, KAVG_ESTATE, "deferred updates and learner-level momentum exclude each other");
     if (!history_dev || ((uintptr_t)history_dev % ALIGN) != 0)
         return fail(c, KAVG_EINVAL, "history block must be a non-null, 256-byte aligned device pointer");

@@ -79,6 +79,10 @@ struct LayerCall {
     int bwd_raw;           // backward-data: write the unmasked fp32 product to dz_prev instead of the masked bf16 one
     int rows;              // update: rows of dz / in to contract over (0: B) -- the steps since the last refresh
     int skip_bias;         // update: leave the bias alone (it is stepped after every local step)
+    // update with fp32 partial outputs instead of a step on the master (long contractions split over
+    // `splits` ranges of rows that run as separate workgroups): partial [P*splits][d_out][d_in],
+    // partial_bias [P*splits][d_out]; B must be a multiple of splits
+    float* partial; float* partial_bias; int splits;
 };
 
 // ---- deferred weight updates (Algorithm 1: every local step adds a rank-B term -lr dZ^T A to the
@@ -129,6 +133,19 @@ bool head_supported(int C);
 hipError_t head_forward_backward(const LayerCall& c, const int32_t* y, const int32_t* idx, long idx_lstride,
                                  float* rowloss, int bf16, hipStream_t st);
 hipError_t head_update(const LayerCall& c, const int32_t* idx, long idx_lstride, int bf16, hipStream_t st);
+
+// ---- convolutional layers (conv.hip): 3x3, stride 1, zero padding 1, channels-last bf16 images ----
+// patches[j][(n,h,w)][(kh,kw,c)] from images in[j][n][h][w][c] (or, with gather, from rows gather[j*gstride+n] of a shared set)
+hipError_t launch_im2col(const void* in, size_t in_lstride, const int32_t* gather, long gstride, void* patches,
+                         int P, int B, int H, int W, int c, hipStream_t st);
+// fp32 per-(position, tap, channel) data gradients folded back onto the image, masked by act > 0, bf16
+hipError_t launch_col2im_mask(const float* draw, const void* act, void* dprev, int P, int B, int H, int W, int c,
+                              hipStream_t st);
+hipError_t launch_pool_forward(const void* act, void* pooled, int P, int B, int HW, int c, hipStream_t st);
+hipError_t launch_pool_backward(const void* dpool, const void* act, void* dz, int P, int B, int HW, int c, hipStream_t st);
+// master -= lr * (sum of the S fp32 partial gradients), weights [n_w] and bias [n_b] of one layer, planes of split.h
+hipError_t launch_conv_step(uint16_t* whi, uint16_t* wlo, uint16_t* bhi, uint16_t* blo, size_t lstride, const float* partial,
+                            const float* pbias, int P, int S, int n_w, int n_b, float lr, hipStream_t st);
 
 // ---- device ceilings (measurement aid) ----
 // one launch of the probe `kind` (KAVG_PROBE_*); *work_out = bytes moved or flops done by it

@@ -21,6 +21,7 @@ EXPORTS = [
     "kavg_momentum", "kavg_replica", "kavg_losses", "kavg_indices", "kavg_round", "kavg_last_error",
     "kavg_destroy", "kavg_meta_update_flat", "kavg_profile", "kavg_profile_read",
     "kavg_velocity_bytes", "kavg_set_learner_momentum", "kavg_velocity", "kavg_graph", "kavg_init_static", "kavg_probe", "kavg_refresh_bytes", "kavg_set_refresh",
+    "kavg_num_params_conv", "kavg_workspace_bytes_conv", "kavg_init_conv",
 ]
 STATIC_WORKSPACE_BYTES = 32 << 20
 CLASS_NAMES = ["index", "forward", "loss", "backward", "update", "meta", "head", "correction"]
@@ -54,6 +55,13 @@ def load_library():
     lib.kavg_num_params.argtypes = [c_int, ip]
     lib.kavg_workspace_bytes.restype = c_sz
     lib.kavg_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, ip, c_int]
+    lib.kavg_num_params_conv.restype = c_sz
+    lib.kavg_num_params_conv.argtypes = [c_int, c_int, c_int, ip, c_int, ip]
+    lib.kavg_workspace_bytes_conv.restype = c_sz
+    lib.kavg_workspace_bytes_conv.argtypes = [c_int, c_int, c_int, c_int, c_int, c_int, ip, c_int, ip]
+    lib.kavg_init_conv.restype = c_int
+    lib.kavg_init_conv.argtypes = [ctypes.POINTER(c_vp), c_int, c_int, c_f, c_f, c_int, c_int, c_int, ip, c_int, ip,
+                                   c_int, ctypes.c_uint64, c_vp, c_sz, c_vp]
     lib.kavg_init.restype = c_int
     lib.kavg_init.argtypes = [ctypes.POINTER(c_vp), c_int, c_int, c_f, c_f, c_int, ip, c_int, c_int,
                               ctypes.c_uint64, c_vp, c_sz, c_vp]
@@ -150,21 +158,36 @@ class MAvg:
     """One kavg_ctx plus the torch tensors it borrows (workspace, data set, indices)."""
 
     def __init__(self, P, K, lr, mu, dims, B, dtype=KAVG_FP32, index_seed=0, device="cuda:0",
-                 static_workspace=False):
+                 static_workspace=False, conv=None):
         """static_workspace: work in the library's own device block (kavg_init_static) instead of a
-        torch allocation."""
+        torch allocation.  conv = (H, W, channels): 3x3 convolutions in front of the MLP
+        (kavg_init_conv; bf16 only)."""
         import torch
         self._torch = torch
         self.lib = load_library()
         self.P, self.K, self.B, self.dims, self.dtype = P, K, B, tuple(int(d) for d in dims), dtype
         self.device = torch.device(device)
         self.ctx = ctypes.c_void_p()
-        nbytes = kavg_workspace_bytes(P, K, B, self.dims, dtype)
+        self.conv = None
+        if conv is not None:
+            H, W, channels = conv
+            self.conv = (int(H), int(W), tuple(int(ch) for ch in channels))
+            assert dtype == KAVG_BF16 and not static_workspace
+            n_conv, ch = len(self.conv[2]) - 1, _dims_array(self.conv[2])
+            nbytes = int(self.lib.kavg_workspace_bytes_conv(P, K, B, H, W, n_conv, ch, len(self.dims) - 1,
+                                                            _dims_array(self.dims)))
+        else:
+            nbytes = kavg_workspace_bytes(P, K, B, self.dims, dtype)
         if nbytes == 0:
             raise KavgError(KAVG_EINVAL, "kavg_workspace_bytes rejected the configuration")
         torch.cuda.set_device(self.device)
         self.stream = torch.cuda.current_stream(self.device)
-        if static_workspace:
+        if conv is not None:
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            rc = self.lib.kavg_init_conv(ctypes.byref(self.ctx), P, K, float(lr), float(mu), H, W, n_conv, ch,
+                                         len(self.dims) - 1, _dims_array(self.dims), B, int(index_seed),
+                                         self.workspace.data_ptr(), nbytes, self.stream.cuda_stream)
+        elif static_workspace:
             self.workspace = None
             rc = self.lib.kavg_init_static(ctypes.byref(self.ctx), P, K, float(lr), float(mu), len(self.dims) - 1,
                                            _dims_array(self.dims), B, dtype, int(index_seed),
@@ -177,6 +200,10 @@ class MAvg:
         if rc != KAVG_OK:
             raise KavgError(rc, self.lib.kavg_last_error(None).decode())
         self.n = kavg_num_params(self.dims)
+        if self.conv is not None:
+            self.n = int(self.lib.kavg_num_params_conv(self.conv[0], self.conv[1], len(self.conv[2]) - 1,
+                                                       _dims_array(self.conv[2]), len(self.dims) - 1,
+                                                       _dims_array(self.dims)))
         self._keep = {}
 
     # -- inputs -----------------------------------------------------------
@@ -196,7 +223,11 @@ class MAvg:
         y_dev: device int32 [N]."""
         torch = self._torch
         assert X_dev.is_cuda and y_dev.is_cuda and X_dev.is_contiguous() and y_dev.is_contiguous()
-        assert y_dev.dtype == torch.int32 and X_dev.shape[1] == self.dims[0]
+        assert y_dev.dtype == torch.int32
+        if self.conv is None:
+            assert X_dev.shape[1] == self.dims[0]
+        else:
+            assert tuple(X_dev.shape[1:]) == (self.conv[0], self.conv[1], self.conv[2][0])
         if self.dtype == KAVG_FP32:
             assert X_dev.dtype == torch.float32
         else:

@@ -93,6 +93,59 @@ def make_workload_inputs(w: Workload, N=None):
     return data
 
 
+def make_image_dataset(N, H, W, c_real, c_pad, n_classes, *, seed_data, seed_texture):
+    """Textured-noise images for the convolutional workload, channels last.
+
+    Class k owns a random 3x3 filter bank F_k [c_real][3][3][c_real]; an image of class k is white
+    Gaussian noise filtered with F_k (circular shifts), so classes differ in their local statistics,
+    which is what 3x3 convolutions followed by a mean over the positions can pick up.  Channels
+    c_real..c_pad-1 are zero (the kernels want channel counts that are multiples of 8).
+    Returns dict(X32 [N][H*W*c_pad] float32 on the bf16 grid, Xbits uint16, y int32 [N])."""
+    rng = np.random.default_rng(seed_data)
+    y = rng.integers(0, n_classes, size=N).astype(np.int32)
+    F = np.random.default_rng(seed_texture).standard_normal((n_classes, c_real, 3, 3, c_real)) / np.sqrt(9.0 * c_real)
+    X = np.zeros((N, H, W, c_pad), dtype=np.float32)
+    bits = np.zeros((N, H, W, c_pad), dtype=np.uint16)
+    chunk = 4096
+    for s in range(0, N, chunk):
+        noise = rng.standard_normal((min(chunk, N - s), H, W, c_real))
+        out = np.zeros_like(noise)
+        yc = y[s:s + chunk]
+        for kh in range(3):
+            for kw in range(3):
+                shifted = np.roll(noise, (1 - kh, 1 - kw), axis=(1, 2))
+                for k in range(n_classes):
+                    sel = yc == k
+                    part = shifted[sel]
+                    out[sel] += (part.reshape(-1, c_real) @ F[k, :, kh, kw, :].T).reshape(part.shape)
+        b, v = snap_to_bf16_grid((out * 1.5).astype(np.float32))
+        X[s:s + chunk, :, :, :c_real] = v
+        bits[s:s + chunk, :, :, :c_real] = b
+    return {"X32": X.reshape(N, -1), "Xbits": bits.reshape(N, -1), "y": y}
+
+
+def he_normal_conv_params(channels, dims, seed) -> np.ndarray:
+    """Flat fp32 vector of a convolutional net: per 3x3 convolution W ~ N(0, 2/(9 c_in)) laid out
+    [c_out][3][3][c_in], then its zero bias; then the MLP as in he_normal_params."""
+    rng = np.random.default_rng(seed)
+    pieces = []
+    for t in range(1, len(channels)):
+        fan_in = 9 * channels[t - 1]
+        pieces.append(rng.standard_normal(channels[t] * fan_in, dtype=np.float32) * np.float32(np.sqrt(2.0 / fan_in)))
+        pieces.append(np.zeros(channels[t], dtype=np.float32))
+    pieces.append(he_normal_params(dims, seed + 1))
+    return np.concatenate(pieces)
+
+
+def make_conv_workload_inputs(w: Workload, N=None):
+    """Images, labels and initial parameters of a convolutional workload (N may be reduced)."""
+    N = w.N if N is None else N
+    data = make_image_dataset(N, w.H, w.W, w.c_real, w.channels[0], w.n_classes,
+                              seed_data=w.seeds["data"], seed_texture=w.seeds["teacher"])
+    data["w0"] = he_normal_conv_params(w.channels, w.dims, w.seeds["init"])
+    return data
+
+
 def make_meta_only_inputs(P, n, seed, base_std=0.05, pert_std=1e-3, v_std=1e-3):
     """Meta-only workload: global model = base ~ N(0, base_std^2); replica j =
     base + N(0, pert_std^2); momentum buffer ~ N(0, v_std^2). All fp32."""

@@ -144,3 +144,17 @@ def test_static_workspace_init_rejects_oversize_before_any_device_call(lib):
     assert rc == kavg.KAVG_EINVAL and not ctx.value
     text = open(os.path.join(ROOT, "include", "kavg.h")).read()
     assert "#define KAVG_STATIC_WORKSPACE_BYTES ((size_t)32 << 20)" in text and kavg.STATIC_WORKSPACE_BYTES == 32 << 20
+
+
+def test_image_generator_is_seeded_padded_and_on_the_bf16_grid():
+    from paper_2110_00625_amd import synth
+    a = synth.make_image_dataset(40, 6, 5, 3, 8, 4, seed_data=5, seed_texture=6)
+    b = synth.make_image_dataset(40, 6, 5, 3, 8, 4, seed_data=5, seed_texture=6)
+    assert np.array_equal(a["Xbits"], b["Xbits"]) and np.array_equal(a["y"], b["y"])
+    X = a["X32"].reshape(40, 6, 5, 8)
+    assert np.all(X[..., 3:] == 0) and np.any(X[..., :3] != 0)
+    assert np.array_equal(X.view(np.uint32) & 0xFFFF, np.zeros(X.shape, dtype=np.uint32))        # exactly representable in bf16
+    assert np.array_equal((X.view(np.uint32) >> 16).astype(np.uint16), a["Xbits"].reshape(X.shape))
+    assert a["y"].min() >= 0 and a["y"].max() < 4
+    w0 = synth.he_normal_conv_params((8, 16), (16, 4), 7)
+    assert w0.size == 16 * 72 + 16 + 4 * 16 + 4 and np.all(w0[16 * 72:16 * 72 + 16] == 0)
