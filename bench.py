@@ -218,6 +218,7 @@ def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration
         torch.cuda.synchronize()
         del src, dst
 
+    fused = g.fused        # small fp32 model: indices, K steps and losses are ONE launch, bracketed as "forward"
     classes = ["index", "forward", "loss", "backward", "update", "meta", "head", "correction"]
     g.profile(classes)
     for _ in range(max(warmup, 1)):
@@ -225,6 +226,8 @@ def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration
         g.meta_update()
     breakdown = g.profile_read()
     heavy = max(("forward", "backward", "update", "meta"), key=lambda c: breakdown[c][0])
+    if fused:
+        heavy = "forward"
 
     # timed region: only the dominant class carries events, and only one launch in EVERY of it
     # (an event pair costs ~10 us of stream time; 17 is coprime with the launches per round, so
@@ -254,6 +257,11 @@ def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration
     per_step = {"meta": 1, "update": n_layers - (1 if head else 0), "forward": n_layers - (1 if head else 0),
                 "backward": n_layers - 1 - (1 if head else 0)}[heavy]
     launches = per_step * per_round * steps
+    if fused:                                                  # the one launch does the work of every class of the K steps
+        launches = steps
+        by = dict(by, forward=sum(by[c] for c in ("forward", "backward", "update")) * w.K)
+        fl = dict(fl, forward=sum(fl[c] for c in ("forward", "backward", "update")) * w.K)
+        per_round = 1
     ms_heavy = ms_sampled / max(sampled, 1) * launches         # sampled mean launch time x all launches of the class
     bytes_heavy = by[heavy] * per_round * steps                # all launches of the class in the timed region
     flops_heavy = fl[heavy] * per_round * steps
@@ -275,7 +283,7 @@ def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration
 
     # all dense products of the local steps against the matrix-core peak (context for the roofline)
     gemm_ms = sum(breakdown[c][0] for c in ("forward", "backward", "update"))
-    gemm_flops = sum(fl[c] for c in ("forward", "backward", "update")) * w.K * max(warmup, 1)
+    gemm_flops = (fl["forward"] if fused else sum(fl[c] for c in ("forward", "backward", "update")) * w.K) * max(warmup, 1)
     local_mfma = {"achieved_TFLOPs": gemm_flops / (gemm_ms * 1e-3) / 1e12, "peak_TFLOPs": peak_flops / 1e12,
                   "frac": gemm_flops / (gemm_ms * 1e-3) / peak_flops,
                   "note": "forward+backward+update launches of the profiled warm-up rounds"}
@@ -283,7 +291,7 @@ def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration
     per_class = {}
     for c in classes:
         ms_c = breakdown[c][0] / max(warmup, 1)
-        if c in by and ms_c > 0 and (refresh == 1 or c == "meta"):
+        if c in by and ms_c > 0 and (refresh == 1 or c == "meta") and not (fused and c != "meta"):
             rounds_bytes = by[c] * (1 if c == "meta" else w.K)
             per_class[c] = {"ms_per_round": ms_c, "hbm_frac": rounds_bytes / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBS}
         else:
@@ -295,7 +303,8 @@ def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration
             w.name, w.P, w.K, w.B, w.mu, w.lr, "-".join(map(str, w.dims)), w.N,
             ", learner momentum %g" % learner_momentum if learner_momentum > 0 else "",
             ", replicas refreshed every %d local steps (deferred updates)" % min(refresh, w.K) if refresh > 1 else ""),
-            "step": "one meta round = K local steps on P learners + fused meta step",
+            "step": "one meta round = K local steps on P learners + fused meta step" + (
+                "; the K local steps run as ONE launch (model on chip)" if fused else ""),
             "samples_per_step": w.P * w.K * w.B, "flops_per_step": flops_per_learner_step(w.dims, w.B) * w.P * w.K},
         "roofline": roof, "local_steps_mfma": local_mfma, "kernel_classes": per_class, "final_mean_loss": loss_last,
     }

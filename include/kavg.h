@@ -143,6 +143,17 @@ int kavg_set_state(kavg_ctx* ctx, const float* w_host, const float* v_host, uint
  * BORROWED.  N in [1, 2^31). */
 int kavg_set_data(kavg_ctx* ctx, const void* X_dev, const int32_t* y_dev, int64_t N);
 
+/* Small fp32 models (KAVG_FP32, one hidden layer of at most 64 units, at most 16 classes, B <= 64,
+ * d_0 a multiple of 4, P * ceil(d_0/64) no larger than the device's number of compute units, no
+ * learner-level momentum) run all K local steps of Algorithm 1 in ONE launch that keeps the
+ * learners' parameters on chip; workgroups of a learner wait for each other through counters in
+ * the workspace, with a bounded number of polls (a wait that gives up makes the next call that
+ * synchronises return KAVG_EDEVICE).  Same arithmetic as the launch-per-layer path up to the order
+ * of fp32 sums.  kavg_fused: 1 when kavg_local_steps takes that path on this context.
+ * kavg_set_fused(ctx, 0) switches it off (the steps then run as separate launches), 1 on again. */
+int kavg_fused(const kavg_ctx* ctx);
+int kavg_set_fused(kavg_ctx* ctx, int on);
+
 /* Minibatch sampling ("randomly sample a mini-batch of size B", Algorithm 1).
  * idx_dev == NULL (default): learner j draws slot s of its t-th local step as
  *   SplitMix64 output number (c+1) of a generator seeded with index_seed,

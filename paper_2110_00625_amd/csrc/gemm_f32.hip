@@ -3,9 +3,10 @@
 //
 // One generic LDS-tiled kernel computes   O[r][c] = sum_k R(r,k) * Cm(c,k)
 // for operands given by (row stride, contraction stride, optional row gather),
-// with three epilogues.  Products and sums are plain fp32 FMAs (no reduced
-// precision matrix path), contraction in ascending k inside each thread, so
-// results are deterministic and independent of timing.
+// with three epilogues.  The contraction runs on the matrix cores in full fp32
+// (v_mfma_f32_32x32x2_f32: exact fp32 products, fp32 accumulation; no reduced
+// precision), each of the four wavefronts owning one 32x32 quarter of the 64x64
+// tile, k ascending, so results are deterministic and independent of timing.
 //
 //   forward        r = sample, c = output unit, k = input unit
 //                  O = act(A_{l-1} W_l^T + b_l)
@@ -30,6 +31,8 @@ constexpr int TILE = 64;   // output tile is TILE x TILE
 constexpr int BK = 32;     // contraction slice
 constexpr int PADW = TILE + 4;
 constexpr int NPER = TILE * BK / 256;   // elements of a slice each thread moves per operand
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 enum { EPI_FWD = 0, EPI_BWD = 1, EPI_UPD = 2, EPI_PARTIAL = 3 };
 
@@ -116,7 +119,8 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(Args a) {
     const int split = blockIdx.z % ((a.nK + a.k_chunk - 1) / a.k_chunk);
     const int learner = blockIdx.z / ((a.nK + a.k_chunk - 1) / a.k_chunk);
     const int r0 = blockIdx.y * TILE, c0 = blockIdx.x * TILE;
-    const int tx = tid & 15, ty = tid >> 4;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int rq = (wave >> 1) * 32, cq = (wave & 1) * 32;    // this wavefront's quarter of the tile
     const int k_begin = split * a.k_chunk;
     const int k_end = k_begin + a.k_chunk < a.nK ? k_begin + a.k_chunk : a.nK;
 
@@ -124,7 +128,7 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(Args a) {
     mover_init(mr, a.R, learner, r0, a.nR, tid);
     mover_init(mc, a.C, learner, c0, a.nC, tid);
 
-    float acc[4][4] = {};
+    f32x16 acc = {};
     float rv_next[NPER], cv_next[NPER];
     mover_load_all(mr, a.R, learner, k_begin, k_end, rv_next);
     mover_load_all(mc, a.C, learner, k_begin, k_end, cv_next);
@@ -139,42 +143,35 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(Args a) {
             mover_load_all(mr, a.R, learner, k0 + BK, k_end, rv_next);      // next slice in flight during the FMAs
             mover_load_all(mc, a.C, learner, k0 + BK, k_end, cv_next);
         }
+        // A step of the matrix instruction takes two k: lane l supplies R(row l%32, k l/32) and Cm(col l%32, k l/32);
+        // consecutive lanes read consecutive LDS words.
 #pragma unroll
-        for (int k = 0; k < BK; ++k) {
-            float rv[4], cv[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { rv[i] = Rs[k][ty * 4 + i]; cv[i] = Cs[k][tx * 4 + i]; }
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(rv[i], cv[j], acc[i][j]);
-        }
+        for (int k = 0; k < BK; k += 2)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(Rs[k + (lane >> 5)][rq + (lane & 31)], Cs[k + (lane >> 5)][cq + (lane & 31)],
+                                                       acc, 0, 0, 0);
         __syncthreads();
     }
 
+    // accumulator v of lane l is the output (row 8*(v/4) + 4*(l/32) + v%4, column l%32) of the quarter
+    const int c = c0 + cq + (lane & 31);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = r0 + ty * 4 + i;
-        if (r >= a.nR) continue;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int c = c0 + tx * 4 + j;
-            if (c >= a.nC) continue;
-            if (EPI == EPI_FWD) {
-                float z = acc[i][j] + a.bias[(size_t)learner * a.bias_stride + c];
-                if (a.relu) z = fmaxf(z, 0.f);
-                a.out[(size_t)learner * a.out_stride + (size_t)r * a.ld_out + c] = z;
-            } else if (EPI == EPI_PARTIAL) {
-                a.out[(size_t)split * a.split_stride + (size_t)learner * a.out_stride + (size_t)r * a.ld_out + c] = acc[i][j];
-            } else if (EPI == EPI_BWD) {
-                const float m = a.mask[(size_t)learner * a.mask_stride + (size_t)r * a.ld_mask + c];
-                a.out[(size_t)learner * a.out_stride + (size_t)r * a.ld_out + c] = m > 0.f ? acc[i][j] : 0.f;
-            } else {
-                const size_t at = (size_t)learner * a.out_stride + (size_t)r * a.ld_out + c;
-                float g = acc[i][j];
-                if (a.u) { g = a.beta * a.u[at] + g; a.u[at] = g; }
-                a.out[at] = a.out[at] - a.lr * g;
-            }
+    for (int v = 0; v < 16; ++v) {
+        const int r = r0 + rq + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (r >= a.nR || c >= a.nC) continue;
+        if (EPI == EPI_FWD) {
+            float z = acc[v] + a.bias[(size_t)learner * a.bias_stride + c];
+            if (a.relu) z = fmaxf(z, 0.f);
+            a.out[(size_t)learner * a.out_stride + (size_t)r * a.ld_out + c] = z;
+        } else if (EPI == EPI_PARTIAL) {
+            a.out[(size_t)split * a.split_stride + (size_t)learner * a.out_stride + (size_t)r * a.ld_out + c] = acc[v];
+        } else if (EPI == EPI_BWD) {
+            const float m = a.mask[(size_t)learner * a.mask_stride + (size_t)r * a.ld_mask + c];
+            a.out[(size_t)learner * a.out_stride + (size_t)r * a.ld_out + c] = m > 0.f ? acc[v] : 0.f;
+        } else {
+            const size_t at = (size_t)learner * a.out_stride + (size_t)r * a.ld_out + c;
+            float g = acc[v];
+            if (a.u) { g = a.beta * a.u[at] + g; a.u[at] = g; }
+            a.out[at] = a.out[at] - a.lr * g;
         }
     }
 

@@ -33,6 +33,8 @@ struct Layout {
     std::vector<size_t> off_patch, off_cact, off_cdz;   // per convolution: patch matrix, output images, their dZ
     std::vector<int> splits;               // ranges of positions its weight gradient is split over
     size_t off_draw = 0, off_pool = 0, off_dpool = 0, off_partial = 0, off_pbias = 0;
+    // all K steps of a small fp32 model in one launch (fused_small.hip): scratch and wait counters; 0 = shape not eligible
+    size_t off_fused = 0;
     size_t total = 0;
 };
 
@@ -104,6 +106,9 @@ Layout make_layout(int P, int K, int B, int L, const int* dims, int dtype, const
             if (splits > 1 && (size_t)splits * P * B * ld * 4 > need) need = (size_t)splits * P * B * ld * 4;
         }
         lo.off_scratch = need ? take(need) : 0;
+        // (sized for a device of up to 256 compute units; the context decides with the real count)
+        if (L == 2 && M == 0 && fused_small_shape_ok(P, K, B, dims[0], dims[1], dims[2], 256))
+            lo.off_fused = take(fused_small_scratch_bytes(P, dims[0]));
     }
     if (M > 0) {
         const size_t rows = (size_t)B * cv.H * cv.W;
@@ -194,6 +199,10 @@ struct kavg_ctx {
     bool warm = false;                  // the sequence has run eagerly once with the current pointers
     hipGraphExec_t gexec = nullptr;
     ConvSpec cv;                        // convolution stack in front of the MLP (empty: plain MLP)
+    bool fused_ok = false;              // the shape and the device allow all K steps in one launch (fused_small.hip)
+    bool fused_on = true;               // ... and the caller has not switched it off (kavg_set_fused)
+    unsigned spin_limit = 1u << 20;     // polls a workgroup of that launch spends on one wait before it gives up
+    uint32_t fused_tag = 0;             // steps that launch has exchanged partials for so far (their tags on the scratch)
     // deferred weight updates (kavg_set_refresh): history block, its carve-up, refresh period
     int refresh = 1;
     char* hist = nullptr;
@@ -233,12 +242,15 @@ int fail(kavg_ctx* c, int code, const char* fmt, ...) {
 
 // wait for the stream, then report (and clear) the device-side range flag
 int sync_and_check(kavg_ctx* c) {
-    int flag = 0;
-    KAVG_HIP(c, hipMemcpyAsync(&flag, c->flag(), sizeof(int), hipMemcpyDeviceToHost, c->stream));
+    int flag[2] = {0, 0};                   // [0] range error, [1] a wait between workgroups gave up
+    KAVG_HIP(c, hipMemcpyAsync(flag, c->flag(), sizeof(flag), hipMemcpyDeviceToHost, c->stream));
     KAVG_HIP(c, hipStreamSynchronize(c->stream));
-    if (flag) {
-        KAVG_HIP(c, hipMemsetAsync(c->flag(), 0, sizeof(int), c->stream));
+    if (flag[0] || flag[1]) {
+        KAVG_HIP(c, hipMemsetAsync(c->flag(), 0, sizeof(flag), c->stream));
         KAVG_HIP(c, hipStreamSynchronize(c->stream));
+        if (flag[1])
+            return fail(c, KAVG_EDEVICE, "a wait between the workgroups of the fused local steps ran out of polls; "
+                        "the replicas are not valid (kavg_set_fused(ctx, 0) runs the steps as separate launches)");
         return fail(c, KAVG_EINVAL, "an index or label outside its range was found on the device");
     }
     return KAVG_OK;
@@ -404,6 +416,13 @@ int init_common(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, 
     c->prof_every = 1;
     for (int k = 0; k < KAVG_NCLASS; ++k) { c->prof_used[k] = 0; c->prof_ms[k] = 0.0; c->prof_launches[k] = 0; c->prof_seen[k] = 0; }
     hipError_t e = hipMemsetAsync(c->flag(), 0, ALIGN, c->stream);
+    if (e == hipSuccess && lo.off_fused) {
+        int dev = 0, cus = 0;
+        e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        c->fused_ok = e == hipSuccess && fused_small_shape_ok(P, K, B, dims[0], dims[1], dims[2], cus);
+        if (e == hipSuccess) e = hipMemsetAsync(c->ws + lo.off_fused, 0, fused_small_scratch_bytes(P, dims[0]), c->stream);
+    }
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) {
         fail(nullptr, KAVG_EDEVICE, "clearing the workspace flag failed: %s", hipGetErrorString(e));
@@ -530,6 +549,16 @@ int kavg_set_data(kavg_ctx* c, const void* X_dev, const int32_t* y_dev, int64_t 
     return KAVG_OK;
 }
 
+int kavg_fused(const kavg_ctx* c) { return c && c->fused_ok && c->fused_on && !c->vel ? 1 : 0; }
+
+int kavg_set_fused(kavg_ctx* c, int on) {
+    if (!c) return KAVG_EINVAL;
+    KAVG_HIP(c, hipStreamSynchronize(c->stream));
+    c->fused_on = on != 0;
+    drop_graph(c);
+    return KAVG_OK;
+}
+
 int kavg_set_indices(kavg_ctx* c, const int32_t* idx_dev) {
     if (!c) return KAVG_EINVAL;
     c->user_idx = idx_dev;
@@ -544,12 +573,40 @@ namespace {
 int issue_steps_deferred(kavg_ctx* c);
 int issue_steps_conv(kavg_ctx* c);
 
+bool fused_now(const kavg_ctx* c) { return c->fused_ok && c->fused_on && !c->vel; }
+
+// Small fp32 model: indices, all K steps and the per-step losses in one launch (fused_small.hip).  The launch
+// carries the step counter (index stream, tags), so it is issued directly, never replayed from a graph.
+int issue_steps_fused(kavg_ctx* c) {
+    hipStream_t st = c->stream;
+    if (c->fused_tag + (uint32_t)c->K + 1u < c->fused_tag) {    // the tags would wrap: start over on a clean scratch
+        KAVG_HIP(c, hipMemsetAsync(c->ws + c->lo.off_fused, 0, fused_small_scratch_bytes(c->P, c->dims[0]), st));
+        c->fused_tag = 0;
+    }
+    FusedSmallCall q{};
+    q.P = c->P; q.K = c->K; q.B = c->B; q.d0 = c->dims[0]; q.d1 = c->dims[1]; q.C = c->dims[2];
+    q.reps = c->reps(); q.rep_stride = c->lo.stride;
+    q.w1_off = c->lo.w_off[0]; q.b1_off = c->lo.b_off[0]; q.w2_off = c->lo.w_off[1]; q.b2_off = c->lo.b_off[1];
+    q.X = (const float*)c->X; q.y = c->y; q.idx = c->idx();
+    q.generate_idx = c->user_idx ? 0 : 1; q.seed = c->seed; q.t0 = c->t0; q.N = (uint32_t)c->N;
+    q.partial = (uint64_t*)(c->ws + c->lo.off_fused);
+    q.tag0 = c->fused_tag;
+    q.err = c->flag() + 1;
+    q.losses = c->losses();
+    q.lr = c->lr; q.spin_limit = c->spin_limit;
+    Bracket br(c, KAVG_CLASS_FORWARD);
+    KAVG_HIP(c, launch_fused_small(q, st));
+    c->fused_tag += (uint32_t)c->K;
+    return KAVG_OK;
+}
+
 int issue_steps(kavg_ctx* c) {
     if (!c->cv.ch.empty()) return issue_steps_conv(c);
     if (c->refresh > 1) return issue_steps_deferred(c);
     hipStream_t st = c->stream;
     const bool bf = c->dtype == KAVG_BF16;
     const int L = c->L;
+
     // With few classes the last layer runs as two dedicated kernels (forward + loss + data gradient,
     // then its update) instead of four generic launches.
     const bool head = head_supported(c->dims[L]);
@@ -887,13 +944,22 @@ int kavg_local_steps(kavg_ctx* c) {
         return fail(c, KAVG_ESTATE, "local step counter would exceed 2^24");
     hipStream_t st = c->stream;
     KAVG_NOTHROW_BEGIN
+    const bool fused = fused_now(c);
     {
         Bracket br(c, KAVG_CLASS_INDEX);
         if (c->user_idx)
             KAVG_HIP(c, launch_index_import(c->idx(), c->user_idx, (size_t)c->P * c->K * c->B, (uint32_t)c->N,
                                             c->flag(), st));
-        else
+        else if (!fused)                        // (the fused launch draws its own indices)
             KAVG_HIP(c, launch_index_stream(c->idx(), c->P, c->K, c->B, c->seed, c->t0, (uint32_t)c->N, st));
+    }
+    if (fused) {
+        const int rc = issue_steps_fused(c);
+        if (rc != KAVG_OK) return rc;
+        c->t0 += (uint32_t)c->K;
+        c->have_steps = true;
+        c->replicas_equal = false;
+        return KAVG_OK;
     }
 
     // Everything after the indices has the same arguments in every round, so it can be replayed.

@@ -147,6 +147,25 @@ hipError_t launch_pool_backward(const void* dpool, const void* act, void* dz, in
 hipError_t launch_conv_step(uint16_t* whi, uint16_t* wlo, uint16_t* bhi, uint16_t* blo, size_t lstride, const float* partial,
                             const float* pbias, int P, int S, int n_w, int n_b, float lr, hipStream_t st);
 
+// ---- all K local steps of a small fp32 model in one launch (fused_small.hip) ----
+struct FusedSmallCall {
+    int P, K, B, d0, d1, C;            // learners, steps, rows; model d0 - d1 - C (one hidden layer)
+    float* reps; size_t rep_stride;    // fp32 replicas; offsets of W_1, b_1, W_2, b_2 inside one
+    size_t w1_off, b1_off, w2_off, b2_off;
+    const float* X; const int32_t* y;  // data set [N][d0], labels
+    int32_t* idx;                      // [P][K][B]: read (generate_idx = 0) or written (1: draws of the index stream)
+    int generate_idx; uint64_t seed; uint32_t t0, N;
+    uint64_t* partial;                 // scratch of fused_small_scratch_bytes: (value, tag) words, zero before the first launch
+    uint32_t tag0;                     // tags of this launch are tag0 + 1 .. tag0 + K; never reused on the same scratch
+    int* err;                          // set to 1 when a reader ran out of polls
+    float* losses;                     // [K][P] mean loss per step and learner
+    float lr; unsigned spin_limit;
+};
+int fused_small_chunks(int d0);
+bool fused_small_shape_ok(int P, int K, int B, int d0, int d1, int C, int compute_units);
+size_t fused_small_scratch_bytes(int P, int d0);
+hipError_t launch_fused_small(const FusedSmallCall& c, hipStream_t st);
+
 // ---- device ceilings (measurement aid) ----
 // one launch of the probe `kind` (KAVG_PROBE_*); *work_out = bytes moved or flops done by it
 hipError_t launch_probe(int kind, void* a, void* b, size_t bytes, int iters, float* sink, hipStream_t st,

@@ -309,6 +309,7 @@ def test_mu_zero_is_plain_averaging():
 def test_profile_counts_launches(dims, fwd_per_step):
     # up to 16 classes the last layer's forward runs inside the loss kernel (one forward launch less)
     g, _o = _pair(2, 3, 0.1, 0.5, dims, 9, False, seed=97)
+    g.set_fused(False)          # the launch-per-layer path is what is counted (a model this small would run its K steps in one launch)
     g.profile(["forward", "update", "meta", "head"], every=1)
     g.local_steps()
     g.meta_update()
