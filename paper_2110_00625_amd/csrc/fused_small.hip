@@ -66,6 +66,7 @@ struct Smem {
     float b1[HID], b2[CLS], rowloss[ROWS];
     int y[ROWS];
     int idx[KBMAX];             // the learner's minibatch indices [K][B]
+    int gave_up;                // a wait ran out of polls
 };
 
 // a partial and its tag as one 64-bit word
@@ -103,11 +104,15 @@ __device__ __forceinline__ float row16_max(float x) {
 }
 
 __global__ void __launch_bounds__(NT)
-fused_small_kernel(FusedSmallCall a, int S, int CW) {
+fused_small_kernel(FusedSmallCall a, int S, int CW, int UH) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     Smem& sm = *(Smem*)smem_raw;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int j = blockIdx.x / S, s = blockIdx.x % S;
+    // workgroup (j, s, h): learner j, column chunk s, and -- with UH = 2 -- half h of the hidden units (the chunk's
+    // two products are then shared by two compute units; everything else is as if UH were 1)
+    const int j = blockIdx.x / (S * UH), s = (blockIdx.x / UH) % S, h = blockIdx.x % UH;
+    const int UN = HID / UH, ub = h * UN;                       // hidden units ub .. ub+UN-1 are this workgroup's
+    const bool first = s == 0 && h == 0;                        // the learner's workgroup that writes what all of them hold
     const int c0 = s * CW;
     const int cw = min(CW, a.d0 - c0);                          // valid columns of this chunk (a multiple of 4)
     const int CW4 = CW / 4;
@@ -119,7 +124,7 @@ fused_small_kernel(FusedSmallCall a, int S, int CW) {
         if (a.generate_idx) {
             const uint64_t c = ((uint64_t)j << 40) | ((uint64_t)(a.t0 + (uint32_t)(e / a.B)) << 16) | (uint32_t)(e % a.B);
             v = (int32_t)(splitmix64_mix(a.seed + (c + 1) * 0x9E3779B97F4A7C15ull) % (uint64_t)a.N);
-            if (s == 0) a.idx[(size_t)j * a.K * a.B + e] = v;
+            if (first) a.idx[(size_t)j * a.K * a.B + e] = v;
         } else {
             v = a.idx[(size_t)j * a.K * a.B + e];
         }
@@ -127,16 +132,17 @@ fused_small_kernel(FusedSmallCall a, int S, int CW) {
     }
 
     // ---- parameters into LDS ----
-    for (int e = tid; e < HID * CW4; e += NT) {
-        const int u = e / CW4, c = (e % CW4) * 4;
+    for (int e = tid; e < UN * CW4; e += NT) {                  // sm.W1 row r holds unit ub + r
+        const int r = e / CW4, c = (e % CW4) * 4;
         f32x4 v = {0.f, 0.f, 0.f, 0.f};
-        if (u < a.d1 && c < cw) v = *(const f32x4*)(rep + a.w1_off + (size_t)u * a.d0 + c0 + c);
-        *(f32x4*)(sm.W1 + u * PW + c) = v;
+        if (ub + r < a.d1 && c < cw) v = *(const f32x4*)(rep + a.w1_off + (size_t)(ub + r) * a.d0 + c0 + c);
+        *(f32x4*)(sm.W1 + r * PW + c) = v;
     }
     for (int e = tid; e < CLS * HID; e += NT) {
         const int c = e / HID, u = e % HID;
         sm.W2[c * PH + u] = (c < a.C && u < a.d1) ? rep[a.w2_off + (size_t)c * a.d1 + u] : 0.f;
     }
+    if (tid == 0) sm.gave_up = 0;
     if (tid < HID) sm.b1[tid] = tid < a.d1 ? rep[a.b1_off + tid] : 0.f;
     if (tid < CLS) sm.b2[tid] = tid < a.C ? rep[a.b2_off + tid] : 0.f;
     for (int e = tid; e < ROWS * PH; e += NT) { sm.D1[e] = 0.f; sm.A1[e] = 0.f; }   // rows beyond B stay zero throughout
@@ -172,6 +178,39 @@ fused_small_kernel(FusedSmallCall a, int S, int CW) {
     const int rblocks = (a.B + 15) / 16;                        // 16-row blocks of the minibatch
     const float invB = 1.f / (float)a.B;
 
+    // The small parameters of step kk, from what its head left in LDS: W_2 <- W_2 - lr dZ_2^T A_1 as four 16x16 blocks
+    // (wavefronts 1..4), b_1 (5), b_2 (6), the loss (7).  Runs while wavefront 0 waits for the next step's partials.
+    auto small_updates = [&](int kk) {
+        if (wave >= 1 && wave <= HID / 16) {
+            const int u0 = (wave - 1) * 16;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            const float* dp = sm.D2 + (lane >> 4) * PD + (lane & 15);           // dZ_2[m][c]: row c of the product
+            const float* ap = sm.A1 + (lane >> 4) * PH + u0 + (lane & 15);
+            for (int m = 0; m < Bk; m += 8) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(dp[m * PD], ap[m * PH], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(dp[(m + 4) * PD], ap[(m + 4) * PH], acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sm.W2[(4 * (lane >> 4) + v) * PH + u0 + (lane & 15)] -= a.lr * acc[v];
+        } else if (wave == 5) {                                 // b_1 <- b_1 - lr colsum(dZ_1)
+            float g = 0.f;
+#pragma unroll 8
+            for (int m = 0; m < Bk; ++m) g += sm.D1[m * PH + lane];
+            sm.b1[lane] -= a.lr * g;
+        } else if (wave == 6) {                                 // b_2 <- b_2 - lr colsum(dZ_2)
+            if (lane < CLS) {
+                float g = 0.f;
+#pragma unroll 8
+                for (int m = 0; m < Bk; ++m) g += sm.D2[m * PD + lane];
+                sm.b2[lane] -= a.lr * g;
+            }
+        } else if (wave == 7 && first && lane == 0) {           // mean loss of this learner's step
+            float l = 0.f;
+            for (int m = 0; m < a.B; ++m) l += sm.rowloss[m];
+            a.losses[(size_t)kk * a.P + j] = l * invB;
+        }
+    };
+
     for (int k = 0; k < a.K; ++k) {
         __syncthreads();                                        // previous step is done with sm.X
 #pragma unroll
@@ -190,8 +229,8 @@ fused_small_kernel(FusedSmallCall a, int S, int CW) {
         //     and receives Zp[m0 + 4*(l/16) + v][u0 + l%16] in accumulator v)
         const uint32_t tag = a.tag0 + (uint32_t)k + 1u;
         uint64_t* part = a.partial + (((size_t)(k & 1) * a.P + j) * S + s) * TILE;
-        for (int blk = wave; blk < rblocks * (HID / 16); blk += NT / 64) {
-            const int m0 = (blk / (HID / 16)) * 16, u0 = (blk % (HID / 16)) * 16;
+        for (int blk = wave; blk < rblocks * (UN / 16); blk += NT / 64) {
+            const int m0 = (blk / (UN / 16)) * 16, u0 = (blk % (UN / 16)) * 16;        // u0: row of sm.W1, unit ub + u0
             f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};   // two chains: the matrix pipeline never waits for its own result
             const float* xp = sm.X + (m0 + (lane & 15)) * PW + (lane >> 4);
             const float* wp = sm.W1 + (u0 + (lane & 15)) * PW + (lane >> 4);
@@ -204,9 +243,31 @@ fused_small_kernel(FusedSmallCall a, int S, int CW) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int m = m0 + 4 * (lane >> 4) + v;
-                if (m < a.B) st_tagged(part + m * HID + u0 + (lane & 15), acc[v], tag);
+                if (m < a.B) st_tagged(part + m * HID + ub + u0 + (lane & 15), acc[v], tag);
             }
         }
+
+        // This wavefront's partials are on their way: say so in its hint word (a separate address: only a hint --
+        // the words of the partials validate themselves).  Then, while wavefront 0 waits for the hints of all
+        // wavefronts of the learner's S workgroups, the others finish the previous step's small parameters.
+        uint32_t* hints = a.hints + ((size_t)(k & 1) * a.P + j) * S * UH * (NT / 64);
+        if (lane == 0) __hip_atomic_store(hints + (s * UH + h) * (NT / 64) + wave, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (wave == 0) {
+            unsigned spins = 0;
+            for (;;) {
+                bool ok = true;
+                for (int i = lane; i < S * UH * (NT / 64); i += 64)
+                    ok = ok && __hip_atomic_load(hints + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == tag;
+                if (__builtin_amdgcn_ballot_w64(!ok) == 0 || gave_up) break;
+                if (++spins >= a.spin_limit) { atomicOr(a.err, 1); sm.gave_up = 1; break; }
+                __builtin_amdgcn_s_sleep(1);
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");       // discard cached copies (see below)
+            }
+        } else if (k > 0) {
+            small_updates(k - 1);
+        }
+        __syncthreads();
+        gave_up = gave_up || sm.gave_up != 0;
 
         // 2. A_1 = relu(sum of the learner's S partials + b_1).  Element e = tid + i*NT of the B x 64 tile; eight
         //    partials of each of four elements are requested together and asked for again until all carry this
@@ -295,12 +356,15 @@ fused_small_kernel(FusedSmallCall a, int S, int CW) {
         }
         __syncthreads();
 
-        // 4. W_1[u][c] <- W_1[u][c] - lr sum_m dZ_1[m][u] X[m][c] on this chunk.  Wavefront w owns the 16 units
-        //    16*(w%4).. and every second 16-column block from w/4 on: one dZ_1 operand feeds all its blocks.
+        // 4. W_1[u][c] <- W_1[u][c] - lr sum_m dZ_1[m][u] X[m][c] on this workgroup's units and columns.  A wavefront
+        //    owns one 16-unit block and every G-th 16-column block (G = wavefronts per unit block): one dZ_1 operand
+        //    feeds all its blocks.
         {
-            const int u0 = (wave & 3) * 16, cb0 = (wave >> 2) * 16;
-            const float* dp = sm.D1 + (lane >> 4) * PH + u0 + (lane & 15);
+            const int nub = UN / 16, G = (NT / 64) / nub;       // 4 unit blocks x 2 column groups, or 2 x 4
+            const int u0 = (wave % nub) * 16, cb0 = (wave / nub) * 16;
+            const float* dp = sm.D1 + (lane >> 4) * PH + ub + u0 + (lane & 15);
             const float* xp = sm.X + (lane >> 4) * PW + cb0 + (lane & 15);
+            const int cstep = 16 * G;
             auto update_w1 = [&](auto nb_tag) {
                 constexpr int NB = decltype(nb_tag)::value;
                 f32x4 acc[NB];
@@ -310,59 +374,35 @@ fused_small_kernel(FusedSmallCall a, int S, int CW) {
                 for (int m = 0; m < Bk; m += 4) {
                     const float d = dp[m * PH];
 #pragma unroll
-                    for (int i = 0; i < NB; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(d, xp[m * PW + 32 * i], acc[i], 0, 0, 0);
+                    for (int i = 0; i < NB; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(d, xp[m * PW + cstep * i], acc[i], 0, 0, 0);
                 }
 #pragma unroll
                 for (int i = 0; i < NB; ++i)
 #pragma unroll
                     for (int v = 0; v < 4; ++v)
-                        sm.W1[(u0 + 4 * (lane >> 4) + v) * PW + cb0 + 32 * i + (lane & 15)] -= a.lr * acc[i][v];
+                        sm.W1[(u0 + 4 * (lane >> 4) + v) * PW + cb0 + cstep * i + (lane & 15)] -= a.lr * acc[i][v];
             };
-            if (CW == 64) update_w1(std::integral_constant<int, 2>{});
-            else if (CW == 128) update_w1(std::integral_constant<int, 4>{});
-            else update_w1(std::integral_constant<int, 6>{});
-        }
-        // the small parameters: W_2 <- W_2 - lr dZ_2^T A_1 as four 16x16 blocks (wavefronts 0..3), b_1, b_2 and the
-        // loss on wavefronts 4..6
-        if (wave < HID / 16) {
-            const int u0 = wave * 16;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            const float* dp = sm.D2 + (lane >> 4) * PD + (lane & 15);           // dZ_2[m][c]: row c of the product
-            const float* ap = sm.A1 + (lane >> 4) * PH + u0 + (lane & 15);
-            for (int m = 0; m < Bk; m += 8) {
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(dp[m * PD], ap[m * PH], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(dp[(m + 4) * PD], ap[(m + 4) * PH], acc, 0, 0, 0);
+            switch ((CW / 16) / G) {                            // column blocks per wavefront
+                case 1: update_w1(std::integral_constant<int, 1>{}); break;
+                case 2: update_w1(std::integral_constant<int, 2>{}); break;
+                case 3: update_w1(std::integral_constant<int, 3>{}); break;
+                case 4: update_w1(std::integral_constant<int, 4>{}); break;
+                default: update_w1(std::integral_constant<int, 6>{}); break;
             }
-#pragma unroll
-            for (int v = 0; v < 4; ++v) sm.W2[(4 * (lane >> 4) + v) * PH + u0 + (lane & 15)] -= a.lr * acc[v];
-        } else if (wave == 4) {                                 // b_1 <- b_1 - lr colsum(dZ_1)
-            float g = 0.f;
-#pragma unroll 8
-            for (int m = 0; m < Bk; ++m) g += sm.D1[m * PH + lane];
-            sm.b1[lane] -= a.lr * g;
-        } else if (wave == 5) {                                 // b_2 <- b_2 - lr colsum(dZ_2)
-            if (lane < CLS) {
-                float g = 0.f;
-#pragma unroll 8
-                for (int m = 0; m < Bk; ++m) g += sm.D2[m * PD + lane];
-                sm.b2[lane] -= a.lr * g;
-            }
-        } else if (wave == 6 && s == 0 && lane == 0) {          // mean loss of this learner's step
-            float l = 0.f;
-            for (int m = 0; m < a.B; ++m) l += sm.rowloss[m];
-            a.losses[(size_t)k * a.P + j] = l * invB;
         }
     }
     __syncthreads();
+    small_updates(a.K - 1);
+    __syncthreads();
 
     // ---- parameters back to the replica ----
-    for (int e = tid; e < HID * CW4; e += NT) {
-        const int u = e / CW4, c = (e % CW4) * 4;
-        if (u < a.d1 && c < cw) {
-            *(f32x4*)(rep + a.w1_off + (size_t)u * a.d0 + c0 + c) = *(const f32x4*)(sm.W1 + u * PW + c);
+    for (int e = tid; e < UN * CW4; e += NT) {
+        const int r = e / CW4, c = (e % CW4) * 4;
+        if (ub + r < a.d1 && c < cw) {
+            *(f32x4*)(rep + a.w1_off + (size_t)(ub + r) * a.d0 + c0 + c) = *(const f32x4*)(sm.W1 + r * PW + c);
         }
     }
-    if (s == 0) {
+    if (first) {
         for (int e = tid; e < a.C * a.d1; e += NT) rep[a.w2_off + e] = sm.W2[(e / a.d1) * PH + e % a.d1];
         if (tid < a.d1) rep[a.b1_off + tid] = sm.b1[tid];
         if (tid < a.C) rep[a.b2_off + tid] = sm.b2[tid];
@@ -385,15 +425,25 @@ bool fused_small_shape_ok(int P, int K, int B, int d0, int d1, int C, int comput
     return (long)P * fused_small_chunks(d0) <= compute_units;
 }
 
-// two buffers of P x chunks tiles of (value, tag) words
-size_t fused_small_scratch_bytes(int P, int d0) { return (size_t)2 * P * fused_small_chunks(d0) * TILE * 8; }
+// Workgroups per column chunk: two (each with half of the hidden units) when the layer is wider than 32 units and
+// the device has the compute units for it.
+int fused_small_unit_split(int P, int d0, int d1, int compute_units) {
+    return d1 > HID / 2 && (long)2 * P * fused_small_chunks(d0) <= compute_units ? 2 : 1;
+}
+
+// two buffers of P x chunks tiles of (value, tag) words, then two of P x chunks x wavefronts hint words
+size_t fused_small_partial_words(int P, int d0) { return (size_t)2 * P * fused_small_chunks(d0) * TILE; }
+size_t fused_small_scratch_bytes(int P, int d0) {          // (hint words for a unit split of two)
+    return fused_small_partial_words(P, d0) * 8 + (size_t)2 * P * fused_small_chunks(d0) * 2 * (NT / 64) * 4;
+}
 
 hipError_t launch_fused_small(const FusedSmallCall& c, hipStream_t st) {
     const int S = fused_small_chunks(c.d0), CW = fused_small_chunk_width(c.d0);
+    const int UH = fused_small_unit_split(c.P, c.d0, c.d1, c.compute_units);
     static hipError_t raised = hipFuncSetAttribute((const void*)fused_small_kernel,
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Smem));
     if (raised != hipSuccess) return raised;
-    hipLaunchKernelGGL(fused_small_kernel, dim3(c.P * S), dim3(NT), sizeof(Smem), st, c, S, CW);
+    hipLaunchKernelGGL(fused_small_kernel, dim3(c.P * S * UH), dim3(NT), sizeof(Smem), st, c, S, CW, UH);
     return hipGetLastError();
 }
 

@@ -202,6 +202,7 @@ struct kavg_ctx {
     bool fused_ok = false;              // the shape and the device allow all K steps in one launch (fused_small.hip)
     bool fused_on = true;               // ... and the caller has not switched it off (kavg_set_fused)
     unsigned spin_limit = 1u << 20;     // polls a workgroup of that launch spends on one wait before it gives up
+    int compute_units = 0;
     uint32_t fused_tag = 0;             // steps that launch has exchanged partials for so far (their tags on the scratch)
     // deferred weight updates (kavg_set_refresh): history block, its carve-up, refresh period
     int refresh = 1;
@@ -420,6 +421,7 @@ int init_common(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, 
         int dev = 0, cus = 0;
         e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        c->compute_units = cus;
         c->fused_ok = e == hipSuccess && fused_small_shape_ok(P, K, B, dims[0], dims[1], dims[2], cus);
         if (e == hipSuccess) e = hipMemsetAsync(c->ws + lo.off_fused, 0, fused_small_scratch_bytes(P, dims[0]), c->stream);
     }
@@ -590,10 +592,12 @@ int issue_steps_fused(kavg_ctx* c) {
     q.X = (const float*)c->X; q.y = c->y; q.idx = c->idx();
     q.generate_idx = c->user_idx ? 0 : 1; q.seed = c->seed; q.t0 = c->t0; q.N = (uint32_t)c->N;
     q.partial = (uint64_t*)(c->ws + c->lo.off_fused);
+    q.hints = (uint32_t*)(q.partial + fused_small_partial_words(c->P, c->dims[0]));
     q.tag0 = c->fused_tag;
     q.err = c->flag() + 1;
     q.losses = c->losses();
     q.lr = c->lr; q.spin_limit = c->spin_limit;
+    q.compute_units = c->compute_units;
     Bracket br(c, KAVG_CLASS_FORWARD);
     KAVG_HIP(c, launch_fused_small(q, st));
     c->fused_tag += (uint32_t)c->K;

@@ -156,14 +156,17 @@ struct FusedSmallCall {
     int32_t* idx;                      // [P][K][B]: read (generate_idx = 0) or written (1: draws of the index stream)
     int generate_idx; uint64_t seed; uint32_t t0, N;
     uint64_t* partial;                 // scratch of fused_small_scratch_bytes: (value, tag) words, zero before the first launch
+    uint32_t* hints;                   // ... followed by the hint words (partial + fused_small_partial_words)
     uint32_t tag0;                     // tags of this launch are tag0 + 1 .. tag0 + K; never reused on the same scratch
     int* err;                          // set to 1 when a reader ran out of polls
     float* losses;                     // [K][P] mean loss per step and learner
     float lr; unsigned spin_limit;
+    int compute_units;                 // of the device (decides whether two workgroups share a column chunk)
 };
 int fused_small_chunks(int d0);
 bool fused_small_shape_ok(int P, int K, int B, int d0, int d1, int C, int compute_units);
 size_t fused_small_scratch_bytes(int P, int d0);
+size_t fused_small_partial_words(int P, int d0);
 hipError_t launch_fused_small(const FusedSmallCall& c, hipStream_t st);
 
 // ---- device ceilings (measurement aid) ----
