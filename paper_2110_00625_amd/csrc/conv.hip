@@ -3,18 +3,27 @@
 //
 // A layer out[n,h,w,o] = b[o] + sum_{kh,kw,c} in[n,h+kh-1,w+kw-1,c] * W[o,kh,kw,c] is the product of the
 // patch matrix  Pm[(n,h,w)][(kh,kw,c)]  (B*H*W rows, 9*c_in columns) with W^T ([c_out][9*c_in], the
-// layer's weights exactly as they lie in the flat parameter vector).  The patch matrix is written
-// out once per layer and step (im2col) and then feeds the same three MFMA products as a dense layer
-// (gemm_bf16.hip): forward, weight gradient + update (its contraction runs over all B*H*W positions),
-// and the data gradient, whose fp32 result per (position, tap, channel) is folded back onto the
-// image (col2im: every input pixel sums the nine taps that touched it), masked by the ReLU of the
-// layer below and rounded to bf16.  Between the last convolution and the MLP sits the mean over the
-// H*W positions.
+// layer's weights exactly as they lie in the flat parameter vector), and its gradients are the two
+// other products of a dense layer on the same matrix (gemm_bf16.hip).
+//
+// Convolutions 2..M never write Pm out: the MFMA kernel's operand loaders form its rows on the fly
+// from the images (ConvDirectLoader / ConvTransLoader: a 16-byte piece of a row is 8 channels of the
+// pixel its tap points at, or zeros outside the image).  Their data gradient is the same kind of
+// product on the dZ images with the taps mirrored and the weights read as [(tap, o)][c_in]
+// (rotate_weights_kernel rebuilds that view from the current weights before every use), so it comes
+// out of the MFMA kernel already masked by the ReLU of the layer below and rounded to bf16.
+//
+// The first convolution gathers its images out of the data set and has only 9*c_0 = 72 columns: its
+// patch matrix is written out (im2col_kernel) and feeds the generic dense kernels.  The same explicit
+// path, with the fp32 product dZ * W per (position, tap, channel) folded back onto the image by
+// col2im_mask_kernel, serves every convolution when an image has 2^14 positions or more (beyond the
+// range of the loaders' multiply-shift divisions).
 //
 // The weight gradient of a convolution has few outputs (c_out x 9 c_in) and a very long contraction;
 // it is split over S ranges of positions that run as separate workgroups (the update kernel writes
 // fp32 partial tiles instead of stepping the master), and conv_step_kernel adds the S partials in
 // ascending order and takes the SGD step of Algorithm 1 on the master's two planes (split.h).
+// Between the last convolution and the MLP sits the mean over the H*W positions.
 #include "kavg_internal.h"
 #include "split.h"
 
@@ -140,6 +149,22 @@ conv_step_kernel(uint16_t* whi, uint16_t* wlo, uint16_t* bhi, uint16_t* blo, siz
     *lo = (uint16_t)split_lo(__builtin_bit_cast(uint32_t, v));
 }
 
+// one lane per 16-byte piece of the rotated weights
+__global__ void __launch_bounds__(256)
+rotate_weights_kernel(const uint16_t* __restrict__ whi, size_t w_lstride, uint16_t* __restrict__ wrot, size_t wrot_lstride,
+                      int c_out, int c_in, size_t per_learner) {
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= per_learner) return;
+    const int j = blockIdx.y;
+    const int c8 = c_in / 8;
+    size_t r = e;
+    const int cc = (int)(r % c8); r /= c8;
+    const int o = (int)(r % c_out);
+    const int tap = (int)(r / c_out);
+    const u32x4 v = *(const u32x4*)(whi + (size_t)j * w_lstride + ((size_t)o * 9 + tap) * c_in + cc * 8);
+    *(u32x4*)(wrot + (size_t)j * wrot_lstride + e * 8) = v;
+}
+
 unsigned blocks(size_t total) { return (unsigned)((total + 255) / 256); }
 
 }  // namespace
@@ -171,6 +196,14 @@ hipError_t launch_pool_backward(const void* dpool, const void* act, void* dz, in
     const size_t total = (size_t)P * B * HW * (c / 8);
     hipLaunchKernelGGL(pool_backward_kernel, dim3(blocks(total)), dim3(256), 0, st, (const uint16_t*)dpool, (const uint16_t*)act,
                        (uint16_t*)dz, HW, c, 1.0f / (float)HW, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_rotate_weights(const uint16_t* whi, size_t w_lstride, uint16_t* wrot, size_t wrot_lstride, int P, int c_out,
+                                 int c_in, hipStream_t st) {
+    const size_t per_learner = (size_t)9 * c_out * (c_in / 8);
+    hipLaunchKernelGGL(rotate_weights_kernel, dim3(blocks(per_learner), P), dim3(256), 0, st, whi, w_lstride, wrot, wrot_lstride,
+                       c_out, c_in, per_learner);
     return hipGetLastError();
 }
 

@@ -65,7 +65,29 @@ struct Operand {
     long gstride;            // per learner
     int n_rows;              // valid memory rows (exact)
     int n_cont;              // readable contiguous extent (multiple of 8)
+    // Implicit patch matrix of a 3x3 convolution (cv_c > 0): `base` is then a channels-last image stack
+    // [n][H][W][cv_c] per learner, memory row x is the position (n, h, w) and the contiguous index is
+    // k = tap * cv_c + channel, tap = 3*kh + kw reading pixel (h + sign*(kh-1), w + sign*(kw-1)), zero outside
+    // the image.  n_rows = positions, n_cont = 9 * cv_c.  div_* are multiply-shift divisors (FastDiv).
+    int cv_c, cv_H, cv_W, cv_sign;
+    uint32_t div_c_m, div_w_m, div_hw_m; int div_c_s, div_w_s, div_hw_s;
 };
+
+// n / d for n < 2^30, d < 2^14 as a multiply and a shift: s = 31 + ceil(log2 d), m = floor(2^s / d) + 1 (< 2^32);
+// the error n * (m d - 2^s) / (d 2^s) stays below 1/d because n < 2^31.
+__device__ __forceinline__ uint32_t fastdiv(uint32_t n, uint32_t m, int s) { return (uint32_t)(((uint64_t)n * m) >> s); }
+inline void fastdiv_make(uint32_t d, uint32_t* m, int* s) {
+    int L = 0;
+    while ((1u << L) < d) ++L;
+    *s = 31 + L;
+    *m = (uint32_t)(((uint64_t)1 << *s) / d) + 1u;
+}
+inline void operand_conv(Operand& o, int c, int H, int W, int sign) {
+    o.cv_c = c; o.cv_H = H; o.cv_W = W; o.cv_sign = sign;
+    fastdiv_make((uint32_t)c, &o.div_c_m, &o.div_c_s);
+    fastdiv_make((uint32_t)W, &o.div_w_m, &o.div_w_s);
+    fastdiv_make((uint32_t)(H * W), &o.div_hw_m, &o.div_hw_s);
+}
 
 struct Args {
     Operand R, C;
@@ -96,6 +118,7 @@ struct Args {
     //                  partial != null: store the fp32 accumulators (and column sums of R) instead of stepping
     //                  the master; "learners" are then ranges of rows of the real learners
     float* partial; float* partial_bias;
+    int cv_splits;                               // implicit C operand with partial outputs: ranges per real learner
 };
 enum { EPI_STD = 0, EPI_GRAM = 1, EPI_RAW = 2, EPI_RELU = 3, EPI_LOGITS = 4 };
 
@@ -195,6 +218,102 @@ struct TransLoader {
         lookup(o, k0 + BK, tid);
 #pragma unroll
         for (int i = 0; i < N; ++i) g.v[i] = *(const u32x4*)(colp + row[i] * o.ld);
+    }
+    __device__ __forceinline__ void store(const StageRegs<N>& g, uint16_t* lds, int tid) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int e = tid + NT * i;
+            const u32x4 zero = {0u, 0u, 0u, 0u};
+            const bool ok = col_ok && ((row_ok >> i) & 1u);
+            *(u32x4*)(lds + (e / (X / 8)) * tpitch(X) + (e % (X / 8)) * 8) = ok ? g.v[i] : zero;
+        }
+    }
+};
+
+// Direct operand that is the implicit patch matrix of a convolution (Operand::cv_c): same pieces and the same LDS
+// tile as DirectLoader; the 8 channels of a piece come from the pixel that the piece's tap points at.
+template <int X, int BK, int NT>
+struct ConvDirectLoader {
+    static constexpr int N = X * BK / 8 / NT;
+    const uint16_t* pixp[N];     // channel 0 of the row's own pixel; null: row outside the operand
+    int h[N], w[N], kc[N];
+    __device__ __forceinline__ void init(const Operand& o, const uint16_t* base, int x0, int tid) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int e = tid + NT * i;
+            const int x = x0 + e / (BK / 8);
+            kc[i] = (e % (BK / 8)) * 8;
+            pixp[i] = nullptr; h[i] = 0; w[i] = 0;
+            if (x < o.n_rows) {
+                const uint32_t pos = (uint32_t)x - fastdiv((uint32_t)x, o.div_hw_m, o.div_hw_s) * (uint32_t)(o.cv_H * o.cv_W);
+                h[i] = (int)fastdiv(pos, o.div_w_m, o.div_w_s);
+                w[i] = (int)pos - h[i] * o.cv_W;
+                pixp[i] = base + (size_t)x * o.cv_c;
+            }
+        }
+    }
+    __device__ __forceinline__ void load(StageRegs<N>& g, const Operand& o, int k0) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            u32x4 val = {0u, 0u, 0u, 0u};
+            const int k = k0 + kc[i];
+            if (pixp[i] && k < o.n_cont) {
+                const int tap = (int)fastdiv((uint32_t)k, o.div_c_m, o.div_c_s);
+                const int ch = k - tap * o.cv_c;
+                const int kh = (tap * 11) >> 5;                  // tap / 3 for tap < 9
+                const int dh = o.cv_sign * (kh - 1), dw = o.cv_sign * (tap - 3 * kh - 1);
+                if ((unsigned)(h[i] + dh) < (unsigned)o.cv_H && (unsigned)(w[i] + dw) < (unsigned)o.cv_W)
+                    val = *(const u32x4*)(pixp[i] + (long)(dh * o.cv_W + dw) * o.cv_c + ch);
+            }
+            g.v[i] = val;
+        }
+    }
+    __device__ __forceinline__ void store(const StageRegs<N>& g, uint16_t* lds, int tid) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int e = tid + NT * i;
+            *(u32x4*)(lds + (e / (BK / 8)) * dpitch(BK) + (e % (BK / 8)) * 8) = g.v[i];
+        }
+    }
+};
+
+// Transposed operand that is the implicit patch matrix of a convolution: memory row = position k (offset by
+// k_off inside the learner's image stack: the launch may hand a workgroup a range of positions), columns = (tap,
+// channel).  A thread's pieces all have the same columns, hence one tap; invalid pieces (outside the image, the
+// operand or the range) are loaded from a safe address and replaced by zeros on their way to LDS, so that no
+// load is predicated.
+template <int X, int BK, int NT>
+struct ConvTransLoader {
+    static constexpr int N = X * BK / 8 / NT;
+    const uint16_t* base;
+    const uint16_t* colp;        // base + (tap offset in pixels) * c + channel: add k * c for the pixel of row k
+    int dh, dw, k_off;
+    bool col_ok;
+    unsigned row_ok;
+    __device__ __forceinline__ void init(const Operand& o, const uint16_t* b, int koff, int x0, int tid) {
+        const int x = x0 + (tid % (X / 8)) * 8;
+        col_ok = x < o.n_cont;
+        const int xx = min(x, o.n_cont - 8);
+        const int tap = (int)fastdiv((uint32_t)xx, o.div_c_m, o.div_c_s);
+        const int ch = xx - tap * o.cv_c;
+        const int kh = (tap * 11) >> 5;
+        dh = o.cv_sign * (kh - 1); dw = o.cv_sign * (tap - 3 * kh - 1);
+        base = b; k_off = koff;
+        colp = b + (long)(dh * o.cv_W + dw) * o.cv_c + ch;
+        row_ok = 0;
+    }
+    __device__ __forceinline__ void load(StageRegs<N>& g, const Operand& o, int k0, int tid) {
+        row_ok = 0;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int kl = k0 + (tid + NT * i) / (X / 8);          // row inside this workgroup's range
+            const uint32_t k = (uint32_t)(k_off + min(kl, o.n_rows - 1));
+            const uint32_t pos = k - fastdiv(k, o.div_hw_m, o.div_hw_s) * (uint32_t)(o.cv_H * o.cv_W);
+            const int h = (int)fastdiv(pos, o.div_w_m, o.div_w_s), w = (int)pos - h * o.cv_W;
+            const bool ok = kl < o.n_rows && (unsigned)(h + dh) < (unsigned)o.cv_H && (unsigned)(w + dw) < (unsigned)o.cv_W;
+            if (ok) row_ok |= 1u << i;
+            g.v[i] = *(const u32x4*)(ok ? colp + (size_t)k * o.cv_c : base);
+        }
     }
     __device__ __forceinline__ void store(const StageRegs<N>& g, uint16_t* lds, int tid) const {
 #pragma unroll
@@ -316,9 +435,12 @@ struct Shape {
 // summed through LDS at the end, in fixed order).  BK = slice length.  One slice is always in
 // flight in registers ahead of the one being multiplied; with PIPE_LDS2 the LDS tiles are double-buffered,
 // so the next slice is written while the current one is read and a slice costs one barrier, not two.
+// CONV_R / CONV_C: that operand is the implicit patch matrix of a convolution (Operand::cv_c).
 template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RTRANS, bool CTRANS, int PIPE, bool SHADOW_CACHED = false,
-          bool GATHER_C = false>
+          bool GATHER_C = false, bool CONV_R = false, bool CONV_C = false>
 __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
+    static_assert(!CONV_R || (!RTRANS && PIPE != PIPE_DMA), "implicit R operand: k-contiguous, staged through registers");
+    static_assert(!CONV_C || (CTRANS && !GATHER_C && MODE == MODE_UPD), "implicit C operand: the update's transposed operand");
     constexpr int NW = WR * WC * WK, NT = 64 * NW;
     constexpr int MR = TR / (32 * WR), MC = TC / (32 * WC);
     static_assert(MR >= 1 && MC >= 1, "tile too small for the wave grid");
@@ -349,6 +471,11 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
 
     const uint16_t* Rbase = a.R.base + (size_t)learner * a.R.lstride;
     const uint16_t* Cbase = a.C.base + (size_t)learner * a.C.lstride;
+    int c_koff = 0;
+    if constexpr (CONV_C) {                     // "learner" = (real learner, range of positions): the image stack is the real learner's
+        Cbase = a.C.base + (size_t)(learner / a.cv_splits) * a.C.lstride;
+        c_koff = (learner % a.cv_splits) * a.C.n_rows;
+    }
     const int32_t* Rg = a.R.gather ? a.R.gather + (long)learner * a.R.gstride : nullptr;
     const int32_t* Cg = a.C.gather ? a.C.gather + (long)learner * a.C.gstride : nullptr;
 
@@ -360,22 +487,28 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    DirectLoader<TR, BK, NT> rdl; TransLoader<TR, BK, NT, false> rtl;
-    DirectLoader<TC, BK, NT> cdl; TransLoader<TC, BK, NT, GATHER_C> ctl;
-    if (RTRANS) rtl.init(a.R, Rbase, Rg, r0, tid); else rdl.init(a.R, Rbase, Rg, r0, tid);
-    if (CTRANS) ctl.init(a.C, Cbase, Cg, c0, tid); else cdl.init(a.C, Cbase, Cg, c0, tid);
+    DirectLoader<TR, BK, NT> rdl; TransLoader<TR, BK, NT, false> rtl; ConvDirectLoader<TR, BK, NT> rcl;
+    DirectLoader<TC, BK, NT> cdl; TransLoader<TC, BK, NT, GATHER_C> ctl; ConvTransLoader<TC, BK, NT> ccl;
+    if constexpr (CONV_R) rcl.init(a.R, Rbase, r0, tid);
+    else if (RTRANS) rtl.init(a.R, Rbase, Rg, r0, tid); else rdl.init(a.R, Rbase, Rg, r0, tid);
+    if constexpr (CONV_C) ccl.init(a.C, Cbase, c_koff, c0, tid);
+    else if (CTRANS) ctl.init(a.C, Cbase, Cg, c0, tid); else cdl.init(a.C, Cbase, Cg, c0, tid);
     StageRegs<TR * BK / 8 / NT> rg;
     StageRegs<TC * BK / 8 / NT> cg;
     float bias_sum = 0.f;                       // update: column sum of dZ for row r0 + tid
     uint32_t touched = 0;                       // update of the first layer: see the prefetch below
 
     auto fetch = [&](int k0) {
-        if (RTRANS) rtl.load(rg, a.R, k0, tid); else rdl.load(rg, a.R, k0);
-        if (CTRANS) ctl.load(cg, a.C, k0, tid); else cdl.load(cg, a.C, k0);
+        if constexpr (CONV_R) rcl.load(rg, a.R, k0);
+        else if (RTRANS) rtl.load(rg, a.R, k0, tid); else rdl.load(rg, a.R, k0);
+        if constexpr (CONV_C) ccl.load(cg, a.C, k0, tid);
+        else if (CTRANS) ctl.load(cg, a.C, k0, tid); else cdl.load(cg, a.C, k0);
     };
     auto stash = [&](int buf) {
-        if (RTRANS) rtl.store(rg, Rs + buf * BUF_ELEMS, tid); else rdl.store(rg, Rs + buf * BUF_ELEMS, tid);
-        if (CTRANS) ctl.store(cg, Cs + buf * BUF_ELEMS, tid); else cdl.store(cg, Cs + buf * BUF_ELEMS, tid);
+        if constexpr (CONV_R) rcl.store(rg, Rs + buf * BUF_ELEMS, tid);
+        else if (RTRANS) rtl.store(rg, Rs + buf * BUF_ELEMS, tid); else rdl.store(rg, Rs + buf * BUF_ELEMS, tid);
+        if constexpr (CONV_C) ccl.store(cg, Cs + buf * BUF_ELEMS, tid);
+        else if (CTRANS) ctl.store(cg, Cs + buf * BUF_ELEMS, tid); else cdl.store(cg, Cs + buf * BUF_ELEMS, tid);
     };
     // Fragments of k slab kq+1 are requested before the MFMAs of slab kq are issued (two register
     // sets, statically indexed), so that the matrix cores do not wait for an LDS round trip per slab.
@@ -517,6 +650,7 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
             long mrow = row;
             if constexpr (GATHER_C) mrow = ((a.next_gather ? a.next_gather : a.C.gather) + (long)learner * a.C.gstride)[row];
             touch_at = (const uint32_t*)(Cbase + mrow * a.C.ld + ln * 64);
+            if constexpr (CONV_C) touch_at = (const uint32_t*)Cbase;     // nothing to prefetch: the images are this launch's own operand
         }
         fetch(0);
         if (MODE == MODE_UPD) {
@@ -743,7 +877,8 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
     }
 }
 
-template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RT, bool CT, int PIPE, bool SC = false, bool GC = false>
+template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RT, bool CT, int PIPE, bool SC = false, bool GC = false,
+          bool CVR = false, bool CVC = false>
 hipError_t launch(Args a, int P, hipStream_t st) {
     a.tiles_c = (a.nC + TC - 1) / TC;
     a.tiles_r = (a.nR + TR - 1) / TR;
@@ -754,12 +889,12 @@ hipError_t launch(Args a, int P, hipStream_t st) {
     static_assert(SMEM <= 160 * 1024, "more LDS than a compute unit has");
     if (SMEM > 64 * 1024) {                     // beyond the default limit: raise it once for this kernel
         static hipError_t raised = hipFuncSetAttribute(
-            (const void*)gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE, SC, GC>,
+            (const void*)gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE, SC, GC, CVR, CVC>,
             hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
         if (raised != hipSuccess) return raised;
     }
-    hipLaunchKernelGGL((gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE, SC, GC>), grid, dim3(64 * WR * WC * WK),
-                       SMEM, st, a);
+    hipLaunchKernelGGL((gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE, SC, GC, CVR, CVC>), grid,
+                       dim3(64 * WR * WC * WK), SMEM, st, a);
     return hipGetLastError();
 }
 
@@ -864,6 +999,60 @@ hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
     }
     if (c.gather) return launch<MODE_UPD, 64, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, true>(a, P, st);
     return launch<MODE_UPD, 64, 128, 2, 2, 1, 64, true, true, PIPE_PLAIN, false, false>(a, P, st);
+}
+
+// ---- 3x3 convolutions on the implicit patch matrix (no im2col): see ConvCall in kavg_internal.h ----
+namespace {
+bool conv_call_ok(const ConvCall& c) {
+    return c.P >= 1 && c.B >= 1 && c.H >= 1 && c.W >= 1 && c.c_in >= 8 && c.c_in % 8 == 0 && c.c_out >= 8 && c.c_out % 8 == 0 &&
+           c.c_in <= 4096 && c.c_out <= 4096 && (long)c.B * c.H * c.W < (1L << 30) && c.H * c.W < (1 << 14) * 4 && c.W < (1 << 14);
+}
+}  // namespace
+
+hipError_t bf16_conv_forward(const ConvCall& c, hipStream_t st) {
+    if (!conv_call_ok(c) || c.H * c.W >= (1 << 14)) return hipErrorInvalidValue;
+    const int rows = c.B * c.H * c.W;
+    Args a = {};
+    a.R = {(const uint16_t*)c.in, (size_t)rows * c.c_in, c.c_in, nullptr, 0, rows, 9 * c.c_in};
+    operand_conv(a.R, c.c_in, c.H, c.W, +1);
+    a.C = {c.ws, c.ws_stride, 9 * c.c_in, nullptr, 0, c.c_out, 9 * c.c_in};
+    a.nR = rows; a.nC = c.c_out; a.nK = 9 * c.c_in;
+    a.bias_hi = c.bhi; a.bias_lo = c.blo; a.bias_lstride = c.ws_stride;
+    a.out = c.out; a.out_lstride = (size_t)rows * c.c_out; a.ld_out = c.c_out; a.relu = 1;
+    if (c.c_out <= 64) return launch<MODE_FWD, 128, 64, 2, 2, 1, 64, false, false, PIPE_PLAIN, false, false, true, false>(a, c.P, st);
+    return launch<MODE_FWD, 128, 128, 2, 2, 1, 64, false, false, PIPE_PLAIN, false, false, true, false>(a, c.P, st);
+}
+
+// dZ_in[n,h,w,ci] = [act_in > 0] * sum_{tap,o} dZ[n, h-(kh-1), w-(kw-1), o] * Wrot[(tap,o)][ci]
+hipError_t bf16_conv_backward_data(const ConvCall& c, hipStream_t st) {
+    if (!conv_call_ok(c) || c.H * c.W >= (1 << 14)) return hipErrorInvalidValue;
+    const int rows = c.B * c.H * c.W;
+    Args a = {};
+    a.R = {(const uint16_t*)c.dz, (size_t)rows * c.c_out, c.c_out, nullptr, 0, rows, 9 * c.c_out};
+    operand_conv(a.R, c.c_out, c.H, c.W, -1);
+    a.C = {c.wrot, c.wrot_stride, c.c_in, nullptr, 0, 9 * c.c_out, c.c_in};        // memory row = k = (tap, o)
+    a.nR = rows; a.nC = c.c_in; a.nK = 9 * c.c_out;
+    a.act_prev = (const uint16_t*)c.in; a.act_lstride = (size_t)rows * c.c_in; a.ld_act = c.c_in;
+    a.out = c.dz_in; a.out_lstride = (size_t)rows * c.c_in; a.ld_out = c.c_in;
+    if (c.c_in <= 64) return launch<MODE_BWD, 128, 64, 2, 2, 1, 64, false, true, PIPE_PLAIN, false, false, true, false>(a, c.P, st);
+    return launch<MODE_BWD, 128, 128, 2, 2, 1, 64, false, true, PIPE_PLAIN, false, false, true, false>(a, c.P, st);
+}
+
+// fp32 partial weight gradients of `splits` ranges of positions per learner (conv_step_kernel adds them)
+hipError_t bf16_conv_update_partial(const ConvCall& c, hipStream_t st) {
+    const int rows = c.B * c.H * c.W;
+    if (!conv_call_ok(c) || c.H * c.W >= (1 << 14) || c.splits < 1 || rows % c.splits != 0 || !c.partial || !c.partial_bias)
+        return hipErrorInvalidValue;
+    const int range = rows / c.splits;
+    Args a = {};
+    a.R = {(const uint16_t*)c.dz, (size_t)range * c.c_out, c.c_out, nullptr, 0, range, c.c_out};      // memory row = k: R(r, k) = dZ[k][r]
+    a.C = {(const uint16_t*)c.in, (size_t)rows * c.c_in, c.c_in, nullptr, 0, range, 9 * c.c_in};
+    operand_conv(a.C, c.c_in, c.H, c.W, +1);
+    a.cv_splits = c.splits;
+    a.nR = c.c_out; a.nC = 9 * c.c_in; a.nK = range;
+    a.ws = c.ws; a.wlo = c.wlo; a.ws_lstride = c.ws_stride; a.bhi = (uint16_t*)c.bhi; a.blo = (uint16_t*)c.blo; a.w_lstride = c.ws_stride;
+    a.partial = c.partial; a.partial_bias = c.partial_bias;
+    return launch<MODE_UPD, 128, 64, 4, 1, 1, 64, true, true, PIPE_PLAIN, true, false, false, true>(a, c.P * c.splits, st);
 }
 
 hipError_t bf16_gram(const GramCall& c, hipStream_t st) {

@@ -33,6 +33,8 @@ struct Layout {
     std::vector<size_t> off_patch, off_cact, off_cdz;   // per convolution: patch matrix, output images, their dZ
     std::vector<int> splits;               // ranges of positions its weight gradient is split over
     size_t off_draw = 0, off_pool = 0, off_dpool = 0, off_partial = 0, off_pbias = 0;
+    bool conv_implicit = false;            // convolutions 2.. form their patch matrices inside the MFMA kernel's loaders
+    size_t off_wrot = 0;                   // ... and their data gradient reads the weights as [(tap, o)][c_in]
     // all K steps of a small fp32 model in one launch (fused_small.hip): scratch and wait counters; 0 = shape not eligible
     size_t off_fused = 0;
     size_t total = 0;
@@ -112,12 +114,15 @@ Layout make_layout(int P, int K, int B, int L, const int* dims, int dtype, const
     }
     if (M > 0) {
         const size_t rows = (size_t)B * cv.H * cv.W;
-        size_t draw = 0, partial = 0, pbias = 0;
+        size_t draw = 0, partial = 0, pbias = 0, wrot = 0;
+        lo.conv_implicit = (size_t)cv.H * cv.W < ((size_t)1 << 14);     // range of the loaders' multiply-shift divisions
         for (int t = 1; t <= M; ++t) {
-            lo.off_patch.push_back(take((size_t)P * rows * 9 * cv.ch[t - 1] * 2));
+            const bool expl = t == 1 || !lo.conv_implicit;             // the first convolution gathers its images: explicit patches
+            lo.off_patch.push_back(expl ? take((size_t)P * rows * 9 * cv.ch[t - 1] * 2) : 0);
             lo.off_cact.push_back(take((size_t)P * rows * cv.ch[t] * 2));
             lo.off_cdz.push_back(take((size_t)P * rows * cv.ch[t] * 2));
-            if (t > 1 && (size_t)P * rows * 9 * cv.ch[t - 1] * 4 > draw) draw = (size_t)P * rows * 9 * cv.ch[t - 1] * 4;
+            if (t > 1 && !lo.conv_implicit && (size_t)P * rows * 9 * cv.ch[t - 1] * 4 > draw) draw = (size_t)P * rows * 9 * cv.ch[t - 1] * 4;
+            if (t > 1 && lo.conv_implicit && (size_t)P * 9 * cv.ch[t] * cv.ch[t - 1] * 2 > wrot) wrot = (size_t)P * 9 * cv.ch[t] * cv.ch[t - 1] * 2;
             // split the weight gradient's contraction until the launch has some hundreds of workgroups,
             // keeping at least 256 positions per range
             const size_t tiles = (size_t)((cv.ch[t] + 127) / 128) * ((9 * cv.ch[t - 1] + 127) / 128) * P;
@@ -129,6 +134,7 @@ Layout make_layout(int P, int K, int B, int L, const int* dims, int dtype, const
             if ((size_t)P * S * cv.ch[t] * 4 > pbias) pbias = (size_t)P * S * cv.ch[t] * 4;
         }
         lo.off_draw = draw ? take(draw) : 0;
+        lo.off_wrot = wrot ? take(wrot) : 0;
         lo.off_pool = take((size_t)P * B * cv.ch[M] * 2);
         lo.off_dpool = take((size_t)P * B * cv.ch[M] * 2);
         lo.off_partial = take(partial);
@@ -713,12 +719,28 @@ int issue_steps_conv(kavg_ctx* c) {
         q.lr = c->lr;
         return q;
     };
+    auto implicit_call = [&](int t) {                               // convolution t >= 2 on the images of convolution t-1
+        ConvCall v{};
+        v.P = P; v.B = B; v.H = H; v.W = W; v.c_in = cv.ch[t - 1]; v.c_out = cv.ch[t];
+        v.ws = c->hi_planes() + lo.cw_off[t - 1]; v.wlo = c->lo_planes() + lo.cw_off[t - 1]; v.ws_stride = lo.stride;
+        v.bhi = c->hi_planes() + lo.cb_off[t - 1]; v.blo = c->lo_planes() + lo.cb_off[t - 1];
+        v.in = c->ws + lo.off_cact[t - 2]; v.out = c->ws + lo.off_cact[t - 1];
+        v.dz = c->ws + lo.off_cdz[t - 1]; v.dz_in = c->ws + lo.off_cdz[t - 2];
+        v.wrot = (const uint16_t*)(c->ws + lo.off_wrot); v.wrot_stride = (size_t)9 * v.c_out * v.c_in;
+        v.partial = (float*)(c->ws + lo.off_partial); v.partial_bias = (float*)(c->ws + lo.off_pbias);
+        v.splits = lo.splits[t - 1];
+        return v;
+    };
     for (int k = 0; k < c->K; ++k) {
         const int32_t* idx_k = c->idx() + (size_t)k * B;
         const long idx_ls = (long)c->K * B;
         float* rowloss_k = c->rowloss() + (size_t)k * P * B;
         for (int t = 1; t <= M; ++t) {                              // convolutions, forward
             Bracket br(c, KAVG_CLASS_FORWARD);
+            if (t > 1 && lo.conv_implicit) {
+                KAVG_HIP(c, bf16_conv_forward(implicit_call(t), st));
+                continue;
+            }
             if (t == 1)
                 KAVG_HIP(c, launch_im2col(c->X, 0, idx_k, idx_ls, c->ws + lo.off_patch[0], P, B, H, W, cv.ch[0], st));
             else
@@ -762,6 +784,20 @@ int issue_steps_conv(kavg_ctx* c) {
                                              P, B, H * W, cv.ch[M], st));
         }
         for (int t = M; t >= 1; --t) {                              // convolutions, backward
+            if (t > 1 && lo.conv_implicit) {
+                ConvCall v = implicit_call(t);
+                {
+                    Bracket br(c, KAVG_CLASS_BACKWARD);
+                    KAVG_HIP(c, launch_rotate_weights(v.ws, lo.stride, (uint16_t*)(c->ws + lo.off_wrot), v.wrot_stride, P,
+                                                      v.c_out, v.c_in, st));
+                    KAVG_HIP(c, bf16_conv_backward_data(v, st));
+                }
+                Bracket br(c, KAVG_CLASS_UPDATE);
+                KAVG_HIP(c, bf16_conv_update_partial(v, st));
+                KAVG_HIP(c, launch_conv_step(v.ws, v.wlo, (uint16_t*)v.bhi, (uint16_t*)v.blo, lo.stride, v.partial, v.partial_bias,
+                                             P, v.splits, v.c_out * 9 * v.c_in, v.c_out, c->lr, st));
+                continue;
+            }
             LayerCall q = conv_call(t);
             if (t > 1) {
                 Bracket br(c, KAVG_CLASS_BACKWARD);

@@ -147,6 +147,26 @@ hipError_t launch_pool_backward(const void* dpool, const void* act, void* dz, in
 hipError_t launch_conv_step(uint16_t* whi, uint16_t* wlo, uint16_t* bhi, uint16_t* blo, size_t lstride, const float* partial,
                             const float* pbias, int P, int S, int n_w, int n_b, float lr, hipStream_t st);
 
+// ---- 3x3 convolution (stride 1, zero padding 1) on channels-last images [P][B][H][W][c], the patch matrix formed
+// inside the operand loaders of the MFMA kernel (no im2col buffer).  Weights [c_out][3][3][c_in] as two planes.
+struct ConvCall {
+    int P, B, H, W, c_in, c_out;
+    uint16_t* ws; uint16_t* wlo; size_t ws_stride;     // hi / lo planes of the weights (first learner), learner stride
+    const uint16_t* bhi; const uint16_t* blo;          // planes of the bias (same stride)
+    const void* in;                                    // input images (bf16): forward and update operand, backward's ReLU mask
+    void* out;                                         // forward: relu(conv + bias), bf16
+    const void* dz;                                    // gradient w.r.t. this layer's pre-activation, bf16 images of c_out channels
+    void* dz_in;                                       // backward: gradient w.r.t. the input layer's pre-activation (masked by in > 0)
+    const uint16_t* wrot; size_t wrot_stride;          // backward: weights as [(tap, o)][c_in] (launch_rotate_weights), learner stride
+    float* partial; float* partial_bias; int splits;   // update: fp32 partials [P*splits][c_out][9 c_in] / [P*splits][c_out]
+};
+hipError_t bf16_conv_forward(const ConvCall& c, hipStream_t st);
+hipError_t bf16_conv_backward_data(const ConvCall& c, hipStream_t st);
+hipError_t bf16_conv_update_partial(const ConvCall& c, hipStream_t st);
+// wrot[j][(tap*c_out + o)*c_in + ci] = whi[j][(o*9 + tap)*c_in + ci]
+hipError_t launch_rotate_weights(const uint16_t* whi, size_t w_lstride, uint16_t* wrot, size_t wrot_lstride, int P, int c_out,
+                                 int c_in, hipStream_t st);
+
 // ---- all K local steps of a small fp32 model in one launch (fused_small.hip) ----
 struct FusedSmallCall {
     int P, K, B, d0, d1, C;            // learners, steps, rows; model d0 - d1 - C (one hidden layer)
