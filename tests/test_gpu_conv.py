@@ -78,6 +78,7 @@ CASES = [
     (3, 2, 10, 6, 5, (8, 8), (8, 10)),                  # one convolution, a one-layer MLP, odd image
     (2, 2, 12, 7, 9, (8, 24, 16, 32), (32, 48, 24)),    # three convolutions, 24 classes (generic last layer)
     (2, 2, 32, 16, 16, (8, 32, 64), (64, 10)),          # 8192 positions per learner: the weight gradient is split
+    (1, 2, 2, 128, 128, (8, 16, 8), (8, 10)),           # 2^14 positions per image: every convolution on explicit patches
 ]
 
 
