@@ -153,6 +153,11 @@ int kavg_set_data(kavg_ctx* ctx, const void* X_dev, const int32_t* y_dev, int64_
  * kavg_set_fused(ctx, 0) switches it off (the steps then run as separate launches), 1 on again. */
 int kavg_fused(const kavg_ctx* ctx);
 int kavg_set_fused(kavg_ctx* ctx, int on);
+/* Polls a workgroup of that launch spends on one wait for the others before it gives up (default 2^20, about a
+ * second).  A wait that gives up never hangs the device: the launch runs to its end, the learners' replicas are
+ * then not valid, and the next call that synchronises returns KAVG_EDEVICE once; install parameters again
+ * (kavg_set_params / kavg_set_state) to go on.  Errors: KAVG_EINVAL for polls < 1. */
+int kavg_set_wait_limit(kavg_ctx* ctx, unsigned polls);
 
 /* Minibatch sampling ("randomly sample a mini-batch of size B", Algorithm 1).
  * idx_dev == NULL (default): learner j draws slot s of its t-th local step as

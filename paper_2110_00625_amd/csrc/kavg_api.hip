@@ -567,6 +567,13 @@ int kavg_set_fused(kavg_ctx* c, int on) {
     return KAVG_OK;
 }
 
+int kavg_set_wait_limit(kavg_ctx* c, unsigned polls) {
+    if (!c) return KAVG_EINVAL;
+    if (polls < 1) return fail(c, KAVG_EINVAL, "the wait limit must be at least one poll");
+    c->spin_limit = polls;
+    return KAVG_OK;
+}
+
 int kavg_set_indices(kavg_ctx* c, const int32_t* idx_dev) {
     if (!c) return KAVG_EINVAL;
     c->user_idx = idx_dev;

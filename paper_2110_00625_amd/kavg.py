@@ -21,7 +21,7 @@ EXPORTS = [
     "kavg_momentum", "kavg_replica", "kavg_losses", "kavg_indices", "kavg_round", "kavg_last_error",
     "kavg_destroy", "kavg_meta_update_flat", "kavg_profile", "kavg_profile_read",
     "kavg_velocity_bytes", "kavg_set_learner_momentum", "kavg_velocity", "kavg_graph", "kavg_init_static", "kavg_probe", "kavg_refresh_bytes", "kavg_set_refresh",
-    "kavg_num_params_conv", "kavg_workspace_bytes_conv", "kavg_init_conv", "kavg_fused", "kavg_set_fused",
+    "kavg_num_params_conv", "kavg_workspace_bytes_conv", "kavg_init_conv", "kavg_fused", "kavg_set_fused", "kavg_set_wait_limit",
 ]
 STATIC_WORKSPACE_BYTES = 32 << 20
 CLASS_NAMES = ["index", "forward", "loss", "backward", "update", "meta", "head", "correction"]
@@ -62,6 +62,8 @@ def load_library():
     lib.kavg_init_conv.restype = c_int
     lib.kavg_init_conv.argtypes = [ctypes.POINTER(c_vp), c_int, c_int, c_f, c_f, c_int, c_int, c_int, ip, c_int, ip,
                                    c_int, ctypes.c_uint64, c_vp, c_sz, c_vp]
+    lib.kavg_set_wait_limit.restype = c_int
+    lib.kavg_set_wait_limit.argtypes = [c_vp, ctypes.c_uint]
     lib.kavg_fused.restype = c_int
     lib.kavg_fused.argtypes = [c_vp]
     lib.kavg_set_fused.restype = c_int
@@ -271,6 +273,9 @@ class MAvg:
 
     def set_fused(self, on):
         _check(self.lib, self.ctx, self.lib.kavg_set_fused(self.ctx, 1 if on else 0))
+
+    def set_wait_limit(self, polls):
+        _check(self.lib, self.ctx, self.lib.kavg_set_wait_limit(self.ctx, int(polls)))
 
     def set_refresh(self, m):
         """Bring the stored replicas up to date every m local steps only (1 = every step, the default);

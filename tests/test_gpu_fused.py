@@ -65,6 +65,28 @@ def test_fused_steps_with_caller_indices():
     assert flat_error(g.params(), o.params()) < TOL_FP32
 
 
+def test_a_wait_that_gives_up_ends_the_launch_and_is_reported():
+    """With a limit of one poll a workgroup does not wait for the others: the launch still runs to its end
+    (nothing hangs), a wait that found its data missing is reported once as KAVG_EDEVICE, and the context
+    works again after the parameters have been installed anew."""
+    P, K, B, dims = 4, 4, 32, (3072, 64, 10)
+    g, o = _pair(P, K, 0.05, 0.9, dims, B, False, 94)
+    w0 = g.params().copy()
+    g.set_wait_limit(1)
+    reported = 0
+    for _ in range(3):
+        g.local_steps()
+        try:
+            g.losses()
+        except kavg.KavgError as e:
+            assert e.code == kavg.KAVG_EDEVICE
+            reported += 1
+    print("launches with a wait that gave up: %d of 3" % reported)
+    g.set_wait_limit(1 << 20)
+    g.set_state(w0, np.zeros_like(w0), 0)                     # parameters, momentum and the index stream as at the start
+    _run_and_compare(g, o, dims, 2, TOL_FP32, "after a wait limit of one poll")
+
+
 def test_fused_path_is_taken_only_where_it_fits():
     _torch()
     assert not kavg.MAvg(2, 2, 0.1, 0.5, (64, 65, 10), 8, kavg.KAVG_FP32).fused          # hidden layer too wide
