@@ -744,57 +744,97 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
 
     // ---- epilogue: lane owns, per block, row r = l%32 and columns 8q + 4(l/32) + 0..3, q = 0..3
     if (MODE != MODE_UPD) {
+        // What the epilogue reads (bias of the lane's columns, ReLU masks of its outputs) is requested here in one
+        // go, before any of it is used: one round trip to memory instead of one per block and column group.
+        u32x2 pbh[MODE == MODE_FWD ? MC : 1][4], pbl[MODE == MODE_FWD ? MC : 1][4];
+        u32x2 pmk[MODE == MODE_BWD ? MR : 1][MODE == MODE_BWD ? MC : 1][4];
+        if (!EARLY) {
+            if constexpr (MODE == MODE_FWD) {
+#pragma unroll
+                for (int j = 0; j < MC; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) bias_raw(j, q, pbh[j][q], pbl[j][q]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < MR; ++i)
+#pragma unroll
+                    for (int j = 0; j < MC; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) pmk[i][j][q] = mask_of(i, j, q);
+            }
+        }
+        // bf16 outputs leave through a per-wavefront LDS patch (the operand tiles are dead by now): the accumulator
+        // layout gives a lane 8 bytes in each of many rows, and stored like that every 128-byte line of the output
+        // is written in sixteen pieces; out of the patch a lane stores 16 bytes and a wavefront whole row segments.
+        constexpr bool STAGED = WK == 1;
+        constexpr int OP = WTC + 8;                             // patch row: the wavefront's columns plus 16 bytes
+        static_assert(!STAGED || NW * 32 * OP * 2 <= SH::SMEM_BYTES, "output patches fit the operand tiles' LDS");
+        const bool bf16_out = MODE == MODE_FWD ? (a.epi == EPI_GRAM || a.relu != 0) : !(a.epi == EPI_RAW || a.epi == EPI_LOGITS);
+        const bool staged = STAGED && bf16_out;
+        uint16_t* opatch = (uint16_t*)smem + wave * 32 * OP;
+        const int c_end = MODE == MODE_FWD ? a.ld_out : a.nC;  // first column that is not stored (a multiple of 8 for bf16 outputs)
 #pragma unroll
         for (int i = 0; i < MR; ++i) {
             const int r = r0 + (wr * MR + i) * 32 + (lane & 31);
-            if (r >= a.nR) continue;
+            const bool r_ok = r < a.nR;
 #pragma unroll
             for (int j = 0; j < MC; ++j) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int c = c0 + (wc * MC + j) * 32 + q * 8 + (lane >> 5) * 4;
+                    const bool ok = r_ok && c < c_end;
                     float v0 = acc[i][j][4 * q + 0], v1 = acc[i][j][4 * q + 1];
                     float v2 = acc[i][j][4 * q + 2], v3 = acc[i][j][4 * q + 3];
+                    u32x2 o;
                     if (MODE == MODE_FWD) {
-                        if (c >= a.ld_out) continue;
                         u32x2 bh2, bl2;
-                        if (EARLY) { bh2 = ebh[q]; bl2 = ebl[q]; } else bias_raw(j, q, bh2, bl2);
+                        if (EARLY) { bh2 = ebh[q]; bl2 = ebl[q]; } else { bh2 = pbh[j][q]; bl2 = pbl[j][q]; }
                         const f32x4 bq = bias_join(bh2, bl2);
                         v0 += bq.x; v1 += bq.y; v2 += bq.z; v3 += bq.w;
                         if (a.epi == EPI_GRAM) {
-                            u32x2 o = {pack2(a.alpha * v0, a.alpha * v1), pack2(a.alpha * v2, a.alpha * v3)};
-                            *(u32x2*)((uint16_t*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
+                            o = (u32x2){pack2(a.alpha * v0, a.alpha * v1), pack2(a.alpha * v2, a.alpha * v3)};
                         } else if (a.relu) {
-                            u32x2 o = {pack2(fmaxf(v0, 0.f), fmaxf(v1, 0.f)), pack2(fmaxf(v2, 0.f), fmaxf(v3, 0.f))};
-                            *(u32x2*)((uint16_t*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
+                            o = (u32x2){pack2(fmaxf(v0, 0.f), fmaxf(v1, 0.f)), pack2(fmaxf(v2, 0.f), fmaxf(v3, 0.f))};
                         } else {
-                            f32x4 o = {v0, v1, v2, v3};
-                            *(f32x4*)((float*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
+                            if (ok) *(f32x4*)((float*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = (f32x4){v0, v1, v2, v3};
+                            continue;
                         }
                     } else {
-                        if (c >= a.nC) continue;
-                        if (a.base) {
+                        if (a.base && ok) {
                             const f32x4 bs = *(const f32x4*)(a.base + (size_t)learner * a.base_lstride + (size_t)r * a.ld_base + c);
                             v0 += bs.x; v1 += bs.y; v2 += bs.z; v3 += bs.w;
                         }
                         if (a.epi == EPI_RAW || a.epi == EPI_LOGITS) {
-                            f32x4 o = {v0, v1, v2, v3};
-                            *(f32x4*)((float*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
+                            if (ok) *(f32x4*)((float*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = (f32x4){v0, v1, v2, v3};
                             continue;
                         }
                         if (a.epi == EPI_RELU) {
                             v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f);
                         } else {
-                            const u32x2 m = EARLY ? emask[q] : mask_of(i, j, q);
+                            const u32x2 m = EARLY ? emask[q] : pmk[i][j][q];
                             // stored activations are relu outputs (never negative): positive <=> non-zero magnitude
                             v0 = (m.x & 0x7FFFu) ? v0 : 0.f;
                             v1 = (m.x & 0x7FFF0000u) ? v1 : 0.f;
                             v2 = (m.y & 0x7FFFu) ? v2 : 0.f;
                             v3 = (m.y & 0x7FFF0000u) ? v3 : 0.f;
                         }
-                        u32x2 o = {pack2(v0, v1), pack2(v2, v3)};
-                        *(u32x2*)((uint16_t*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
+                        o = (u32x2){pack2(v0, v1), pack2(v2, v3)};
                     }
+                    if (staged) *(u32x2*)(opatch + (lane & 31) * OP + j * 32 + q * 8 + (lane >> 5) * 4) = o;
+                    else if (ok) *(u32x2*)((uint16_t*)a.out + (size_t)learner * a.out_lstride + (size_t)r * a.ld_out + c) = o;
+                }
+            }
+            if (staged) {
+                // (the patch is this wavefront's own, and a wavefront's LDS accesses complete in order)
+                constexpr int CPRW = WTC / 8, RPP = 64 / CPRW;  // 16-byte chunks per patch row, rows per pass
+                const int rblk = r0 + (wr * MR + i) * 32;
+#pragma unroll
+                for (int pass = 0; pass < 32 / RPP; ++pass) {
+                    const int row = pass * RPP + lane / CPRW, ch = lane % CPRW;
+                    const int rr = rblk + row, cc = c0 + wc * WTC + ch * 8;
+                    const u32x4 v = *(const u32x4*)(opatch + row * OP + ch * 8);
+                    if (rr < a.nR && cc < c_end)
+                        *(u32x4*)((uint16_t*)a.out + (size_t)learner * a.out_lstride + (size_t)rr * a.ld_out + cc) = v;
                 }
             }
         }
