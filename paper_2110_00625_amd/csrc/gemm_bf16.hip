@@ -39,6 +39,7 @@
 // memory-contiguous extent is a multiple of 8 elements (hidden widths are
 // required to be, the class count is padded in the logits / dZ_L buffers).
 #include "kavg_internal.h"
+#include "fastdiv.h"
 #include "split.h"
 
 namespace kavg {
@@ -73,15 +74,6 @@ struct Operand {
     uint32_t div_c_m, div_w_m, div_hw_m; int div_c_s, div_w_s, div_hw_s;
 };
 
-// n / d for n < 2^30, d < 2^14 as a multiply and a shift: s = 31 + ceil(log2 d), m = floor(2^s / d) + 1 (< 2^32);
-// the error n * (m d - 2^s) / (d 2^s) stays below 1/d because n < 2^31.
-__device__ __forceinline__ uint32_t fastdiv(uint32_t n, uint32_t m, int s) { return (uint32_t)(((uint64_t)n * m) >> s); }
-inline void fastdiv_make(uint32_t d, uint32_t* m, int* s) {
-    int L = 0;
-    while ((1u << L) < d) ++L;
-    *s = 31 + L;
-    *m = (uint32_t)(((uint64_t)1 << *s) / d) + 1u;
-}
 inline void operand_conv(Operand& o, int c, int H, int W, int sign) {
     o.cv_c = c; o.cv_H = H; o.cv_W = W; o.cv_sign = sign;
     fastdiv_make((uint32_t)c, &o.div_c_m, &o.div_c_s);

@@ -158,3 +158,32 @@ def test_image_generator_is_seeded_padded_and_on_the_bf16_grid():
     assert a["y"].min() >= 0 and a["y"].max() < 4
     w0 = synth.he_normal_conv_params((8, 16), (16, 4), 7)
     assert w0.size == 16 * 72 + 16 + 4 * 16 + 4 and np.all(w0[16 * 72:16 * 72 + 16] == 0)
+
+
+def test_multiply_shift_division_is_exact_over_its_stated_range(tmp_path):
+    """csrc/fastdiv.h replaces n / d by (n * m) >> s in the index arithmetic of the convolution loaders.  Its
+    own functions, compiled for the host, against integer division: every divisor below 2^14, with the
+    numerators where a wrong constant shows first (multiples of d and their neighbours up to 2^30) and
+    random ones."""
+    src = tmp_path / "fd.cpp"
+    src.write_text(
+        '#include "%s"\n'
+        'extern "C" long check(const unsigned* n, long count, unsigned dmax) {\n'
+        '  long bad = 0;\n'
+        '  for (unsigned d = 1; d < dmax; ++d) { unsigned m; int s; kavg::fastdiv_make(d, &m, &s);\n'
+        '    for (long i = 0; i < count; ++i) bad += kavg::fastdiv(n[i], m, s) != n[i] / d;\n'
+        '    const unsigned top = (1u << 30) - 1; const unsigned q = top / d;\n'
+        '    for (unsigned k = 0; k < 64 && k <= q; ++k) { const unsigned a = (q - k) * d;\n'
+        '      bad += kavg::fastdiv(a, m, s) != a / d; if (a) bad += kavg::fastdiv(a - 1, m, s) != (a - 1) / d;\n'
+        '      if (a + d - 1 <= top) bad += kavg::fastdiv(a + d - 1, m, s) != (a + d - 1) / d; }\n'
+        '    bad += kavg::fastdiv(top, m, s) != top / d; }\n'
+        '  return bad; }\n'
+        % os.path.join(ROOT, "paper_2110_00625_amd", "csrc", "fastdiv.h"))
+    so = tmp_path / "fd.so"
+    subprocess.run(["g++", "-O2", "-shared", "-fPIC", str(src), "-o", str(so)], check=True)
+    lib = ctypes.CDLL(str(so))
+    lib.check.restype = ctypes.c_long
+    lib.check.argtypes = [ctypes.c_void_p, ctypes.c_long, ctypes.c_uint]
+    rng = np.random.default_rng(11)
+    n = np.concatenate([rng.integers(0, 1 << 30, size=3000, dtype=np.uint64), np.arange(0, 70000, 7, dtype=np.uint64)]).astype(np.uint32)
+    assert lib.check(n.ctypes.data, n.size, 1 << 14) == 0
