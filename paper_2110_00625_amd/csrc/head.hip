@@ -290,6 +290,8 @@ __device__ __forceinline__ void load_dz_row(const void* dz, size_t at, int ldz, 
 // blockIdx.x*16 + 4*wave + pl of the layer's input units.  Every lane sums dZ_L[s][c] * A[s][piece]
 // over its samples in ascending order; a butterfly over the group bits of the lane index adds the
 // sixteen groups, after which lane group g applies the update of class c = g.
+constexpr int XCH_CS = 16 * 32 + 36;      // floats between classes in a wavefront's exchange patch (36: classes fall on different banks)
+
 template <bool BF16, int CT>
 __global__ void __launch_bounds__(256) head_update_kernel(HeadArgs a) {
     constexpr int N = Piece<BF16>::N;
@@ -328,14 +330,37 @@ __global__ void __launch_bounds__(256) head_update_kernel(HeadArgs a) {
     for (int c = 0; c < CT; ++c) {
         float b = bsum[c];
         bsum[c] = groups_sum(b);
-#pragma unroll
-        for (int e = 0; e < N; ++e) {
-            float v = acc[c][e];
-            acc[c][e] = groups_sum(v);
-        }
     }
-    if (live && grp < a.C) {
-        float mine[N];
+    float mine[N];
+    if constexpr (BF16) {
+        // Lane group g needs class g's gradient of the wavefront's four pieces, summed over the sixteen sample
+        // groups: each lane leaves its CT x 8 partial sums in the wavefront's LDS patch and lane group g adds
+        // the sixteen partials of class g in ascending group order (a butterfly would move every value four
+        // times, this moves it twice).  A wavefront's LDS accesses complete in order: no barrier.
+        extern __shared__ __align__(16) float head_xch[];
+        float* patch = head_xch + wave * (CT * XCH_CS);
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            *(f32x4*)(patch + c * XCH_CS + lane * 8) = (f32x4){acc[c][0], acc[c][1], acc[c][2], acc[c][3]};
+            *(f32x4*)(patch + c * XCH_CS + lane * 8 + 4) = (f32x4){acc[c][4], acc[c][5], acc[c][6], acc[c][7]};
+        }
+#pragma unroll
+        for (int e = 0; e < N; ++e) mine[e] = 0.f;
+        const float* src = patch + min(grp, CT - 1) * XCH_CS + pl * 8;
+#pragma unroll
+        for (int g2 = 0; g2 < 16; ++g2) {
+            const f32x4 lo4 = *(const f32x4*)(src + g2 * 32), hi4 = *(const f32x4*)(src + g2 * 32 + 4);
+            mine[0] += lo4.x; mine[1 % N] += lo4.y; mine[2 % N] += lo4.z; mine[3 % N] += lo4.w;
+            mine[4 % N] += hi4.x; mine[5 % N] += hi4.y; mine[6 % N] += hi4.z; mine[7 % N] += hi4.w;
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+#pragma unroll
+            for (int e = 0; e < N; ++e) {
+                float v = acc[c][e];
+                acc[c][e] = groups_sum(v);
+            }
 #pragma unroll
         for (int e = 0; e < N; ++e) mine[e] = 0.f;
 #pragma unroll
@@ -344,6 +369,8 @@ __global__ void __launch_bounds__(256) head_update_kernel(HeadArgs a) {
 #pragma unroll
                 for (int e = 0; e < N; ++e) mine[e] = acc[c][e];
             }
+    }
+    if (live && grp < a.C) {
         const size_t uat = (size_t)learner * a.w_lstride + (size_t)grp * a.d + (size_t)q * N;   // velocity (fp32 layout)
         if (a.u) {                                            // heavy ball inside the learner
 #pragma unroll
@@ -423,12 +450,23 @@ void launch_fb(const HeadArgs& a, dim3 grid, hipStream_t st) {
     const int pieces = a.d / Piece<BF16>::N;
     if (pieces <= 128) launch_fb2<BF16, true>(a, grid, st); else launch_fb2<BF16, false>(a, grid, st);
 }
+template <bool BF16, int CT>
+hipError_t launch_upd_ct(const HeadArgs& a, dim3 grid, hipStream_t st) {
+    constexpr int SMEM = BF16 ? 4 * CT * XCH_CS * 4 : 0;       // one exchange patch per wavefront
+    if (SMEM > 64 * 1024) {
+        static hipError_t raised = hipFuncSetAttribute((const void*)head_update_kernel<BF16, CT>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+        if (raised != hipSuccess) return raised;
+    }
+    hipLaunchKernelGGL((head_update_kernel<BF16, CT>), grid, dim3(256), SMEM, st, a);
+    return hipSuccess;
+}
 template <bool BF16>
-void launch_upd(const HeadArgs& a, dim3 grid, hipStream_t st) {
-    if (a.C <= 4) hipLaunchKernelGGL((head_update_kernel<BF16, 4>), grid, dim3(256), 0, st, a);
-    else if (a.C <= 8) hipLaunchKernelGGL((head_update_kernel<BF16, 8>), grid, dim3(256), 0, st, a);
-    else if (a.C <= 12) hipLaunchKernelGGL((head_update_kernel<BF16, 12>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((head_update_kernel<BF16, 16>), grid, dim3(256), 0, st, a);
+hipError_t launch_upd(const HeadArgs& a, dim3 grid, hipStream_t st) {
+    if (a.C <= 4) return launch_upd_ct<BF16, 4>(a, grid, st);
+    if (a.C <= 8) return launch_upd_ct<BF16, 8>(a, grid, st);
+    if (a.C <= 12) return launch_upd_ct<BF16, 12>(a, grid, st);
+    return launch_upd_ct<BF16, 16>(a, grid, st);
 }
 
 }  // namespace
@@ -445,8 +483,8 @@ hipError_t head_update(const LayerCall& c, const int32_t* idx, long idx_lstride,
     HeadArgs a = make_args(c, nullptr, idx, idx_lstride, nullptr, bf16 != 0);
     const int pieces = c.d_in / (bf16 ? 8 : 1);
     dim3 grid((pieces + 15) / 16, c.P);
-    if (bf16) launch_upd<true>(a, grid, st); else launch_upd<false>(a, grid, st);
-    return hipGetLastError();
+    const hipError_t e = bf16 ? launch_upd<true>(a, grid, st) : launch_upd<false>(a, grid, st);
+    return e != hipSuccess ? e : hipGetLastError();
 }
 
 }  // namespace kavg
