@@ -224,8 +224,13 @@ def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration
 
     fused = g.fused        # small fp32 model: indices, K steps and losses are ONE launch, bracketed as "forward"
     classes = ["index", "forward", "loss", "backward", "update", "meta", "head", "correction"]
+    bracketed = max(warmup, 1)
+    if warmup >= 2:                      # the first round pays one-off costs (code upload, cold caches): untimed, unbracketed
+        g.local_steps()
+        g.meta_update()
+        bracketed = warmup - 1
     g.profile(classes)
-    for _ in range(max(warmup, 1)):
+    for _ in range(bracketed):
         g.local_steps()
         g.meta_update()
     breakdown = g.profile_read()
@@ -287,14 +292,14 @@ def run_workload(torch, w, steps, warmup, learner_momentum=0.0, copy_calibration
 
     # all dense products of the local steps against the matrix-core peak (context for the roofline)
     gemm_ms = sum(breakdown[c][0] for c in ("forward", "backward", "update"))
-    gemm_flops = (fl["forward"] if fused else sum(fl[c] for c in ("forward", "backward", "update")) * w.K) * max(warmup, 1)
+    gemm_flops = (fl["forward"] if fused else sum(fl[c] for c in ("forward", "backward", "update")) * w.K) * bracketed
     local_mfma = {"achieved_TFLOPs": gemm_flops / (gemm_ms * 1e-3) / 1e12, "peak_TFLOPs": peak_flops / 1e12,
                   "frac": gemm_flops / (gemm_ms * 1e-3) / peak_flops,
                   "note": "forward+backward+update launches of the profiled warm-up rounds"}
     # every class against the HBM roofline, from the bracketed warm-up rounds
     per_class = {}
     for c in classes:
-        ms_c = breakdown[c][0] / max(warmup, 1)
+        ms_c = breakdown[c][0] / bracketed
         if c in by and ms_c > 0 and (refresh == 1 or c == "meta") and not (fused and c != "meta"):
             rounds_bytes = by[c] * (1 if c == "meta" else w.K)
             per_class[c] = {"ms_per_round": ms_c, "hbm_frac": rounds_bytes / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBS}
@@ -325,8 +330,13 @@ def run_conv_workload(torch, w, steps, warmup):
     g.set_data(X, torch.from_numpy(data["y"]).cuda())
     g.set_params(data["w0"])
     classes = ["index", "forward", "loss", "backward", "update", "meta", "head"]
+    bracketed = max(warmup, 1)
+    if warmup >= 2:                      # the first round pays one-off costs: untimed, unbracketed
+        g.local_steps()
+        g.meta_update()
+        bracketed = warmup - 1
     g.profile(classes)
-    for _ in range(max(warmup, 1)):
+    for _ in range(bracketed):
         g.local_steps()
         g.meta_update()
     breakdown = g.profile_read()
@@ -351,7 +361,7 @@ def run_conv_workload(torch, w, steps, warmup):
                    "samples_per_step": w.P * w.K * w.B, "flops_per_step": flops},
         "flops_fraction_of_bf16_mfma_peak": flops / (dt / steps) / (MFMA_BF16_PEAK_TFLOPS * 1e12),
         "achieved_TFLOPs": flops / (dt / steps) / 1e12,
-        "kernel_classes": {c: {"ms_per_round": breakdown[c][0] / max(warmup, 1)} for c in classes},
+        "kernel_classes": {c: {"ms_per_round": breakdown[c][0] / bracketed} for c in classes},
         "final_mean_loss": loss_last,
     }
 
