@@ -103,7 +103,7 @@ int kavg_init(kavg_ctx** out, int P, int K, float lr, float mu,
  * kavg_num_params_conv / kavg_workspace_bytes_conv: length of the flat vector / bytes of workspace,
  * 0 for a configuration kavg_init_conv would refuse.
  * Errors: as kavg_init, plus KAVG_EINVAL for H or W outside [1,4096], n_conv outside [1,63], a
- * channel count that is not a multiple of 8 in [8,4096], B*H*W >= 2^30, dims[0] != channels[n_conv]. */
+ * channel count that is not a multiple of 8 in [8,2048], B*H*W >= 2^30, dims[0] != channels[n_conv]. */
 size_t kavg_num_params_conv(int H, int W, int n_conv, const int* channels, int n_layers, const int* dims);
 size_t kavg_workspace_bytes_conv(int P, int K, int B, int H, int W, int n_conv, const int* channels,
                                  int n_layers, const int* dims);

@@ -95,18 +95,37 @@ col2im_mask_kernel(const float* __restrict__ draw, const uint16_t* __restrict__ 
     *(u32x4*)(dprev + e * 8) = o;
 }
 
-// pooled[j,n,c] = bf16(mean over the H*W positions), summed in ascending order; one lane per (j,n,c)
+// pooled[j,n,c] = bf16(mean over the H*W positions).  One workgroup per image: a lane owns 8 channels and every
+// G-th position (G = 256 / (c/8) position groups, 16-byte loads), the G partial sums of a channel meet in LDS and
+// are added in ascending group order -- a fixed summation order.
 __global__ void __launch_bounds__(256)
-pool_forward_kernel(const uint16_t* __restrict__ act, uint16_t* __restrict__ pooled, int HW, int c, float inv, size_t total) {
-    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= total) return;
-    const size_t img = e / c;
-    const int cc = (int)(e % c);
-    const uint16_t* p = act + img * (size_t)HW * c + cc;
-    float s = 0.f;
-#pragma unroll 8
-    for (int i = 0; i < HW; ++i) s += __builtin_bit_cast(float, (uint32_t)p[(size_t)i * c] << 16);
-    pooled[e] = bf16_bits(s * inv);
+pool_forward_kernel(const uint16_t* __restrict__ act, uint16_t* __restrict__ pooled, int HW, int c, float inv) {
+    __shared__ float part[256 * 8];
+    const int c8 = c / 8;                                     // lanes per position (<= 256: c <= 2048)
+    const int G = 256 / c8;                                   // position groups
+    const int tid = threadIdx.x, cc = tid % c8, g = tid / c8;
+    const size_t img = blockIdx.x;
+    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (g < G) {
+        const uint16_t* p = act + img * (size_t)HW * c + cc * 8;
+#pragma unroll 4
+        for (int i = g; i < HW; i += G) {
+            const u32x4 v = *(const u32x4*)(p + (size_t)i * c);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                s[2 * q] += __builtin_bit_cast(float, v[q] << 16);
+                s[2 * q + 1] += __builtin_bit_cast(float, v[q] & 0xFFFF0000u);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part[(g * c8 + cc) * 8 + e] = s[e];
+    }
+    __syncthreads();
+    for (int ch = tid; ch < c; ch += 256) {
+        float t = 0.f;
+        for (int g2 = 0; g2 < G; ++g2) t += part[(g2 * c8 + ch / 8) * 8 + ch % 8];
+        pooled[img * c + ch] = bf16_bits(t * inv);
+    }
 }
 
 // dz[j,n,hw,c] = bf16( [act > 0] * dpool[j,n,c] / (H*W) ), 8 channels per lane
@@ -186,9 +205,9 @@ hipError_t launch_col2im_mask(const float* draw, const void* act, void* dprev, i
 }
 
 hipError_t launch_pool_forward(const void* act, void* pooled, int P, int B, int HW, int c, hipStream_t st) {
-    const size_t total = (size_t)P * B * c;
-    hipLaunchKernelGGL(pool_forward_kernel, dim3(blocks(total)), dim3(256), 0, st, (const uint16_t*)act, (uint16_t*)pooled, HW, c,
-                       1.0f / (float)HW, total);
+    if (c < 8 || c % 8 != 0 || c > 2048) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(pool_forward_kernel, dim3((unsigned)((size_t)P * B)), dim3(256), 0, st, (const uint16_t*)act, (uint16_t*)pooled, HW, c,
+                       1.0f / (float)HW);
     return hipGetLastError();
 }
 

@@ -46,7 +46,7 @@ struct ConvSpec { int H = 0, W = 0; std::vector<int> ch; };
 bool conv_ok(const ConvSpec& cv, int L, const int* dims, int dtype, int B) {
     if (cv.ch.empty()) return true;
     if (dtype != KAVG_BF16 || cv.H < 1 || cv.W < 1 || cv.H > 4096 || cv.W > 4096 || cv.ch.size() < 2 || cv.ch.size() > 64) return false;
-    for (int c : cv.ch) if (c < 8 || c % 8 != 0 || c > 4096) return false;
+    for (int c : cv.ch) if (c < 8 || c % 8 != 0 || c > 2048) return false;
     if ((size_t)B * cv.H * cv.W >= ((size_t)1 << 30)) return false;
     return dims[0] == cv.ch.back();
 }
@@ -398,7 +398,7 @@ int init_common(kavg_ctx** out, int P, int K, float lr, float mu, int n_layers, 
                     "dims >= 1 and, for bf16, d_0..d_{L-1} multiples of 8");
     if (!conv_ok(cv, n_layers, dims, dtype, B))
         return fail(nullptr, KAVG_EINVAL, "bad convolution stack: need bf16, H,W in [1,4096], channel counts that are "
-                    "multiples of 8 in [8,4096], B*H*W < 2^30 and d_0 equal to the last channel count");
+                    "multiples of 8 in [8,2048], B*H*W < 2^30 and d_0 equal to the last channel count");
     if (!(lr >= 0.f) || !std::isfinite(lr)) return fail(nullptr, KAVG_EINVAL, "lr must be finite and >= 0");
     if (!(mu >= 0.f && mu < 1.f)) return fail(nullptr, KAVG_EINVAL, "mu must lie in [0,1)");
     if (!workspace_dev || ((uintptr_t)workspace_dev % ALIGN) != 0)
