@@ -5,7 +5,9 @@
 // step; run as a chain of generic kernels it is bound by ~6 dependent launches per step.  Here the
 // learner's first-layer weights are cut into S column chunks of CW input features (CW a multiple of
 // 64, at most 192); workgroup (j, s) keeps chunk s of learner j's W_1 in LDS for the whole call,
-// together with private copies of b_1, W_2 and b_2.  Per step
+// together with private copies of b_1, W_2 and b_2.  (Where the device has the compute units for it and the
+// layer has more than 32 units, two workgroups share a chunk, each with half of the hidden units: "its chunk"
+// is then those units' rows of the chunk; everything else is unchanged.)  Per step
 //   1. the workgroup multiplies its CW columns of the gathered rows X[idx] with its chunk of W_1
 //      (fp32 matrix instructions) and writes the B x 64 partial pre-activations to device memory;
 //   2. it collects the partials of all S workgroups of its learner and adds them in ascending chunk
@@ -16,16 +18,18 @@
 //   4. and takes the SGD step on its own chunk of W_1 in LDS (dZ_1^T times its columns of X[idx]).
 // Only after the K steps do the parameters go back to the replica in device memory.
 //
-// One exchange per step, without flags or fences: a partial is written as a 64-bit word (value, tag) by one
-// device-scope atomic store, the tag being the number of the step counted over all launches of the
+// One exchange per step, without flags that anything depends on: a partial is written as a 64-bit word
+// (value, tag) by one device-scope atomic store, the tag being the number of the step counted over all launches of the
 // context.  A reader requests the S words of an element with device-scope atomic loads and asks again
 // (a bounded number of times, after a device-scope acquire that discards cached copies of the lines)
 // until every tag shows the current step; each word validates itself, so nothing depends on the order
-// in which different addresses become visible.  Partials alternate
-// between two buffers: a workgroup overwrites the buffer of step k only when it computes step k+2,
+// in which different addresses become visible.  (Each wavefront also raises a hint word after its stores, and
+// wavefront 0 waits for the learner's hints before anyone gathers -- the other wavefronts finish the previous
+// step's W_2, b_1, b_2 and loss meanwhile; the hints only time the first request, the tags decide.)  Partials
+// alternate between two buffers: a workgroup overwrites the buffer of step k only when it computes step k+2,
 // which it starts after it has read every partial of step k+1, each of which was written after its
-// writer had read the partials of step k.  All P*S workgroups must be resident at once: the host
-// launches this kernel only when P*S does not exceed the number of compute units.  A reader that
+// writer had read the partials of step k.  All workgroups must be resident at once: the host
+// launches this kernel only when their number does not exceed the number of compute units.  A reader that
 // runs out of polls raises an error word and carries on, so every wavefront reaches the end of the
 // kernel whatever happens.
 //
