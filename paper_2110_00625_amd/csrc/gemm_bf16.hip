@@ -56,7 +56,11 @@ enum { MODE_FWD = 0, MODE_BWD = 1, MODE_UPD = 2 };
 // Main-loop pipelines.  PLAIN: one LDS buffer, the next slice waits in registers.  LDS2: two LDS
 // buffers, the next slice is written while the current one is read.  DMA: two LDS buffers filled by
 // direct global->LDS loads (no registers, no LDS store instructions); k-contiguous operands only.
-enum { PIPE_PLAIN = 0, PIPE_LDS2 = 1, PIPE_DMA = 2 };
+// RING: a ring of LDS buffers filled, slices ahead, by two extra wavefronts that do nothing else
+// (the wavefronts that multiply never issue a memory load, so none of them stands in the queue of the
+// memory pipeline while its MFMAs could run); whole slices only.
+enum { PIPE_PLAIN = 0, PIPE_LDS2 = 1, PIPE_DMA = 2, PIPE_RING = 3 };
+constexpr int RING_LOADERS = 2, RING_BYTES = 144 * 1024;
 
 struct Operand {
     const uint16_t* base;    // learner 0
@@ -350,8 +354,8 @@ __device__ __forceinline__ bf16x8 frag_trans(const uint16_t* tile, int block_x0,
 // stored.  A chunk beyond the contraction length is clamped too and zeroed in LDS after it has
 // landed (fix_tail), by the lane that loaded it.
 template <int BK> __device__ __forceinline__ int dma_swizzle(int x) {
-    static_assert(BK == 128 || BK == 64, "rows of 256 bytes (one per bank period) or 128 bytes (two)");
-    return BK == 128 ? (x & 15) : ((x >> 1) & 7);
+    static_assert(BK == 128 || BK == 64 || BK == 32, "rows of 256 bytes (one per bank period), 128 bytes (two) or 64 bytes (four)");
+    return BK == 128 ? (x & 15) : BK == 64 ? ((x >> 1) & 7) : ((x >> 2) & 3);
 }
 
 template <int X, int BK, int NT>
@@ -411,10 +415,12 @@ struct Shape {
     static constexpr int MR = TR / (32 * WR), MC = TC / (32 * WC);
     static constexpr int WTC = MC * 32;                 // columns of a wavefront's tile
     static constexpr int SPITCH = WTC + 4;              // update epilogue: fp32 staging row, padded
-    static constexpr bool DIRECT = PIPE == PIPE_DMA;       // global -> LDS loads, unpadded swizzled tiles
+    static constexpr bool DIRECT = PIPE == PIPE_DMA || PIPE == PIPE_RING;       // global -> LDS loads, unpadded swizzled tiles
+    static constexpr int THREADS = 64 * (WR * WC * WK + (PIPE == PIPE_RING ? RING_LOADERS : 0));
     static constexpr int R_ELEMS = DIRECT ? TR * BK : RTRANS ? BK * tpitch(TR) : TR * dpitch(BK);
     static constexpr int C_ELEMS = DIRECT ? TC * BK : CTRANS ? BK * tpitch(TC) : TC * dpitch(BK);
-    static constexpr int OPER_BYTES = (PIPE == PIPE_PLAIN ? 1 : 2) * (R_ELEMS + C_ELEMS) * 2;
+    static constexpr int RING_BUFS = RING_BYTES / ((R_ELEMS + C_ELEMS) * 2);
+    static constexpr int OPER_BYTES = (PIPE == PIPE_PLAIN ? 1 : PIPE == PIPE_RING ? RING_BUFS : 2) * (R_ELEMS + C_ELEMS) * 2;
     static constexpr int STAGE_BYTES = MODE == MODE_UPD ? 4 * 32 * SPITCH * 4 : 0;
     static constexpr int KRED_BYTES = WK > 1 ? WR * WC * MR * MC * 16 * 64 * 4 : 0;   // one k group's partial tiles
     static constexpr int SMEM1 = OPER_BYTES > STAGE_BYTES ? OPER_BYTES : STAGE_BYTES;
@@ -430,7 +436,7 @@ struct Shape {
 // CONV_R / CONV_C: that operand is the implicit patch matrix of a convolution (Operand::cv_c).
 template <int MODE, int TR, int TC, int WR, int WC, int WK, int BK, bool RTRANS, bool CTRANS, int PIPE, bool SHADOW_CACHED = false,
           bool GATHER_C = false, bool CONV_R = false, bool CONV_C = false>
-__global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
+__global__ void __launch_bounds__(64 * (WR * WC * WK + (PIPE == PIPE_RING ? RING_LOADERS : 0))) gemm_bf16_kernel(Args a) {
     static_assert(!CONV_R || (!RTRANS && PIPE != PIPE_DMA), "implicit R operand: k-contiguous, staged through registers");
     static_assert(!CONV_C || (CTRANS && !GATHER_C && MODE == MODE_UPD), "implicit C operand: the update's transposed operand");
     constexpr int NW = WR * WC * WK, NT = 64 * NW;
@@ -438,7 +444,8 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
     static_assert(MR >= 1 && MC >= 1, "tile too small for the wave grid");
     static_assert((BK / 16) % WK == 0, "slice must split evenly over the k groups");
     static_assert(MODE != MODE_UPD || (WK == 1 && NW == 4 && PIPE == PIPE_PLAIN), "the update epilogue assumes 4 wavefronts, no k split, one LDS buffer");
-    constexpr bool DIRECT = PIPE == PIPE_DMA;
+    constexpr bool DIRECT = PIPE == PIPE_DMA || PIPE == PIPE_RING;
+    static_assert(PIPE != PIPE_RING || (WK == 1 && MODE != MODE_UPD), "ring pipeline: forward / backward-data without a k split");
     static_assert(NT % (TR / 8) == 0 && NT % (TC / 8) == 0, "loader column mapping");
     typedef Shape<MODE, TR, TC, WR, WC, WK, BK, RTRANS, CTRANS, PIPE> SH;
     constexpr int WTC = SH::WTC, SPITCH = SH::SPITCH, R_ELEMS = SH::R_ELEMS, C_ELEMS = SH::C_ELEMS;
@@ -481,10 +488,12 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
 
     DirectLoader<TR, BK, NT> rdl; TransLoader<TR, BK, NT, false> rtl; ConvDirectLoader<TR, BK, NT> rcl;
     DirectLoader<TC, BK, NT> cdl; TransLoader<TC, BK, NT, GATHER_C> ctl; ConvTransLoader<TC, BK, NT> ccl;
-    if constexpr (CONV_R) rcl.init(a.R, Rbase, r0, tid);
-    else if (RTRANS) rtl.init(a.R, Rbase, Rg, r0, tid); else rdl.init(a.R, Rbase, Rg, r0, tid);
-    if constexpr (CONV_C) ccl.init(a.C, Cbase, c_koff, c0, tid);
-    else if (CTRANS) ctl.init(a.C, Cbase, Cg, c0, tid); else cdl.init(a.C, Cbase, Cg, c0, tid);
+    if constexpr (!DIRECT) {                    // (direct global->LDS pipelines set up their own loaders below)
+        if constexpr (CONV_R) rcl.init(a.R, Rbase, r0, tid);
+        else if (RTRANS) rtl.init(a.R, Rbase, Rg, r0, tid); else rdl.init(a.R, Rbase, Rg, r0, tid);
+        if constexpr (CONV_C) ccl.init(a.C, Cbase, c_koff, c0, tid);
+        else if (CTRANS) ctl.init(a.C, Cbase, Cg, c0, tid); else cdl.init(a.C, Cbase, Cg, c0, tid);
+    }
     StageRegs<TR * BK / 8 / NT> rg;
     StageRegs<TC * BK / 8 / NT> cg;
     float bias_sum = 0.f;                       // update: column sum of dZ for row r0 + tid
@@ -600,7 +609,57 @@ __global__ void __launch_bounds__(64 * WR * WC * WK) gemm_bf16_kernel(Args a) {
         }
     }
 
-    if constexpr (PIPE == PIPE_DMA) {
+    if constexpr (PIPE == PIPE_RING) {
+        static_assert(!RTRANS && !CTRANS, "direct LDS loads: k-contiguous operands only");
+        // Slice s lives in buffer s % NB and is requested NB - 1 slices ahead, both operands alike: the
+        // memory pipeline of a compute unit hands loads back in the order they were issued, so the
+        // activations (cache hits) cannot overtake the weights (which come from memory, once each) and
+        // gain nothing from being requested later.  Barrier s (one per slice, all wavefronts): the
+        // loaders arrive once slice s has landed, the multipliers once they are done with slice s-1;
+        // after it the loaders refill the buffer of slice s-1.  The loaders' barrier carries no fence:
+        // a fence would make them wait for everything they have requested.
+        constexpr int NB = SH::RING_BUFS, D = NB - 1;
+        constexpr int LN = (TR + TC) * BK / 8 / (64 * RING_LOADERS);     // loads per loader wavefront and slice
+        static_assert(D >= 1 && D <= 5 && D * LN <= 63, "the slices in flight must fit the wavefront's load counter");
+        const int slices = a.nK / BK;               // (whole slices: checked by the launcher)
+        if (__builtin_amdgcn_readfirstlane(wave) >= NW) {
+            DmaLoader<TR, BK, 64 * RING_LOADERS> rdma; DmaLoader<TC, BK, 64 * RING_LOADERS> cdma;
+            rdma.init(a.R, Rbase, Rg, r0, tid - NT);
+            cdma.init(a.C, Cbase, Cg, c0, tid - NT);
+#pragma unroll
+            for (int d = 0; d < D; ++d)
+                if (d < slices) {
+                    rdma.template load<true>(a.R, d * BK, Rs + d * BUF_ELEMS);
+                    cdma.template load<true>(a.C, d * BK, Cs + d * BUF_ELEMS);
+                }
+            int fill = D;                           // buffer of slice s + D
+            for (int s = 0; s < slices; ++s) {
+                // slice s has landed when at most the younger ones are on their way
+                switch (min(D - 1, slices - 1 - s)) {
+                    case 4: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(D > 4 ? 4 * LN : 0) : "memory"); break;
+                    case 3: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(D > 3 ? 3 * LN : 0) : "memory"); break;
+                    case 2: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(D > 2 ? 2 * LN : 0) : "memory"); break;
+                    case 1: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(D > 1 ? LN : 0) : "memory"); break;
+                    default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                }
+                asm volatile("s_barrier" ::: "memory");
+                if (s + D < slices) {
+                    rdma.template load<true>(a.R, (s + D) * BK, Rs + fill * BUF_ELEMS);
+                    cdma.template load<true>(a.C, (s + D) * BK, Cs + fill * BUF_ELEMS);
+                }
+                fill = fill == NB - 1 ? 0 : fill + 1;
+            }
+            asm volatile("s_barrier" ::: "memory");
+            return;
+        }
+        int buf = 0;
+        for (int s = 0; s < slices; ++s) {
+            __syncthreads();
+            multiply(buf);
+            buf = buf == NB - 1 ? 0 : buf + 1;
+        }
+        __syncthreads();                                // tiles are dead: the epilogue reuses their LDS
+    } else if constexpr (PIPE == PIPE_DMA) {
         static_assert(!RTRANS && !CTRANS && MODE != MODE_UPD, "direct LDS loads: k-contiguous operands only");
         DmaLoader<TR, BK, NT> rdma; DmaLoader<TC, BK, NT> cdma;
         rdma.init(a.R, Rbase, Rg, r0, tid);
@@ -925,25 +984,27 @@ hipError_t launch(Args a, int P, hipStream_t st) {
             hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
         if (raised != hipSuccess) return raised;
     }
+    if (PIPE == PIPE_RING && (a.nK % BK != 0 || a.nK > a.R.n_cont || a.nK > a.C.n_cont)) return hipErrorInvalidValue;
     hipLaunchKernelGGL((gemm_bf16_kernel<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE, SC, GC, CVR, CVC>), grid,
-                       dim3(64 * WR * WC * WK), SMEM, st, a);
+                       dim3(Shape<MODE, TR, TC, WR, WC, WK, BK, RT, CT, PIPE>::THREADS), SMEM, st, a);
     return hipGetLastError();
 }
 
 int round8(int x) { return (x + 7) / 8 * 8; }
 
 // Launch shapes: rows x columns of the output tile (_K2: eight wavefronts, two k groups, slices of 128).
-enum { T128x128 = 0, T128x64 = 1, T64x128 = 2, T64x64_K2 = 3 };
+enum { T128x128 = 0, T128x64 = 1, T64x128 = 2, T64x64_K2 = 3, T256x128 = 4 };
 
 // Measured on MI355X over the workload shapes (batch 64..256, widths 1024..4096, 8..32 learners):
 // with >= 512 tiles of 128x128 the launch fills the chip with the tile that reads LDS least per
 // flop; smaller problems are LDS- and barrier-bound per workgroup, and the 64x64 tile with two k
 // groups (most wavefronts per compute unit, half as many barriers per k) wins.
-int pick_tile(int mode, int nR, int nC, int P) {
+int pick_tile(int mode, int nR, int nC, int nK, int P) {
     const long tiles128 = (long)((nR + 127) / 128) * ((nC + 127) / 128) * P;
     // few output columns (convolution channels): a 64-column tile wastes least
     if (nC <= 64 && nR > 64 && tiles128 >= 512) return T128x64;
     if (mode == MODE_FWD) {
+        if (nR % 256 == 0 && nK % 64 == 0 && nK >= 128 && (long)(nR / 256) * ((nC + 127) / 128) * P >= 192) return T256x128;
         if (nR <= 64) return (long)((nC + 127) / 128) * P >= 512 ? T64x128 : T64x64_K2;
         return tiles128 >= 512 ? T128x128 : T64x64_K2;
     }
@@ -962,6 +1023,9 @@ hipError_t launch_tiled(const Args& a, int P, int tile, hipStream_t st) {
             // through registers at the 4096-wide layers
             if constexpr (MODE == MODE_FWD) return launch<MODE, 128, 128, 2, 2, 1, 64, RT, CT, PIPE_DMA>(a, P, st);
             else return launch<MODE, 128, 128, 2, 2, 1, 64, RT, CT, PIPE_PLAIN>(a, P, st);
+        case T256x128:
+            if constexpr (MODE == MODE_FWD) return launch<MODE, 256, 128, 2, 2, 1, 64, RT, CT, PIPE_RING>(a, P, st);
+            else return hipErrorInvalidValue;
         case T128x64:  return launch<MODE, 128, 64, 2, 2, 1, 64, RT, CT, PIPE_PLAIN>(a, P, st);
         case T64x128:  return launch<MODE, 64, 128, 2, 2, 1, 64, RT, CT, PIPE_PLAIN>(a, P, st);
         default:
@@ -982,7 +1046,7 @@ hipError_t bf16_forward(const LayerCall& c, hipStream_t st) {
     a.nR = c.B; a.nC = c.d_out; a.nK = c.d_in;
     a.bias_hi = c.bhi; a.bias_lo = c.blo; a.bias_lstride = c.ws_stride;
     a.out = c.out; a.out_lstride = c.out_stride; a.ld_out = c.ld_out; a.relu = c.relu;
-    return launch_tiled<MODE_FWD, false, false>(a, c.P, pick_tile(MODE_FWD, a.nR, a.nC, c.P), st);
+    return launch_tiled<MODE_FWD, false, false>(a, c.P, pick_tile(MODE_FWD, a.nR, a.nC, a.nK, c.P), st);
 }
 
 hipError_t bf16_backward_data(const LayerCall& c, hipStream_t st) {
@@ -993,7 +1057,7 @@ hipError_t bf16_backward_data(const LayerCall& c, hipStream_t st) {
     a.act_prev = (const uint16_t*)c.in; a.act_lstride = c.in_stride; a.ld_act = c.ld_in;
     a.out = c.dz_prev; a.out_lstride = c.dz_prev_stride; a.ld_out = c.ld_in;
     if (c.bwd_raw) { a.epi = EPI_RAW; a.act_prev = nullptr; }
-    return launch_tiled<MODE_BWD, false, true>(a, c.P, pick_tile(MODE_BWD, a.nR, a.nC, c.P), st);
+    return launch_tiled<MODE_BWD, false, true>(a, c.P, pick_tile(MODE_BWD, a.nR, a.nC, a.nK, c.P), st);
 }
 
 hipError_t bf16_update(const LayerCall& c, hipStream_t st) {
@@ -1094,7 +1158,7 @@ hipError_t bf16_gram(const GramCall& c, hipStream_t st) {
     a.nR = c.nR; a.nC = c.nC; a.nK = c.nK;
     a.out = c.out; a.out_lstride = c.out_stride; a.ld_out = c.ld_out; a.relu = 1;
     a.epi = EPI_GRAM; a.alpha = c.alpha;
-    return launch_tiled<MODE_FWD, false, false>(a, c.P, pick_tile(MODE_FWD, a.nR, a.nC, c.P), st);
+    return launch_tiled<MODE_FWD, false, false>(a, c.P, pick_tile(MODE_FWD, a.nR, a.nC, a.nK, c.P), st);
 }
 
 hipError_t bf16_apply(const ApplyCall& c, hipStream_t st) {
@@ -1109,7 +1173,7 @@ hipError_t bf16_apply(const ApplyCall& c, hipStream_t st) {
     } else {
         a.epi = c.epi == KAVG_APPLY_RELU ? EPI_RELU : EPI_LOGITS;
     }
-    return launch_tiled<MODE_BWD, false, true>(a, c.P, pick_tile(MODE_BWD, a.nR, a.nC, c.P), st);
+    return launch_tiled<MODE_BWD, false, true>(a, c.P, pick_tile(MODE_BWD, a.nR, a.nC, a.nK, c.P), st);
 }
 
 namespace {

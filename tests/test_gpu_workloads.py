@@ -323,6 +323,34 @@ def test_large_tile_shapes_on_ragged_extents(P, B, sample):
     g.close()
 
 
+# The 256x128 forward tile whose slices are brought in by loader wavefronts through a ring of LDS buffers
+# (batches that are multiples of 256, contraction lengths that are multiples of 64, at least 192 tiles):
+# the shortest contractions it takes (two and three slices: fewer than the ring is deep), a ragged last
+# column tile (3000 = 23 x 128 + 56), gathered rows in layer 1, two row tiles per learner.
+@pytest.mark.parametrize("P,B,dims", [(8, 256, (128, 3000, 24)), (8, 256, (192, 3000, 24)), (4, 512, (448, 3000, 3008, 16))],
+                         ids=["two_slices", "three_slices", "two_row_tiles"])
+def test_ring_forward_tile_on_short_and_ragged_extents(P, B, dims):
+    torch = _torch()
+    N, lr = 1200, 0.05
+    data = synth.make_dataset(N, dims[0], dims[-1], bf16=True, seed_data=91, seed_teacher=92, teacher_hidden=32)
+    w0 = synth.he_normal_params(dims, 93)
+    g = kavg.MAvg(P, 1, lr, 0.9, dims, B, kavg.KAVG_BF16, index_seed=94)
+    g.set_data(torch.from_numpy(data["Xbits"].view(np.int16)).cuda(), torch.from_numpy(data["y"]).cuda())
+    g.set_params(w0)
+    o = O.MAvgOracle(P, 1, lr, 0.9, dims, B, bf16=True, index_seed=94)
+    o.set_data(data["X32"], data["y"])
+    o.set_params(w0)
+    g.local_steps()
+    sample = (0, P - 1)
+    o.local_steps(learners=list(sample))
+    for j in sample:
+        e = replica_error(g.replica(j), o.replica(j), dims)
+        print("ring forward P=%d B=%d dims=%s learner %d: %.3g" % (P, B, dims, j, e))
+        assert e < 2e-3
+        assert abs(g.losses()[0, j] - o.losses()[0, j]) < 1e-3 * max(1.0, o.losses()[0, j])
+    g.close()
+
+
 @pytest.mark.parametrize("w", [CIFAR_MLP, NOISY_WIDE, LARGE], ids=lambda w: w.name)
 def test_meta_step_at_workload_size_with_shadows(w):
     torch = _torch()
