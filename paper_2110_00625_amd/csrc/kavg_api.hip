@@ -12,6 +12,7 @@
 
 #include "../../include/kavg.h"
 #include "kavg_internal.h"
+#include "conv_wgrad.h"
 #include "split.h"
 
 using namespace kavg;
@@ -32,6 +33,7 @@ struct Layout {
     std::vector<size_t> cw_off, cb_off;    // parameter offsets of the convolutions (they come first in the flat vector)
     std::vector<size_t> off_patch, off_cact, off_cdz;   // per convolution: patch matrix, output images, their dZ
     std::vector<int> splits;               // ranges of positions its weight gradient is split over
+    std::vector<int> splits_halo;          // the same for the all-taps weight-gradient kernel; 0: shape not covered
     size_t off_draw = 0, off_pool = 0, off_dpool = 0, off_partial = 0, off_pbias = 0;
     bool conv_implicit = false;            // convolutions 2.. form their patch matrices inside the MFMA kernel's loaders
     size_t off_wrot = 0;                   // ... and their data gradient reads the weights as [(tap, o)][c_in]
@@ -129,6 +131,9 @@ Layout make_layout(int P, int K, int B, int L, const int* dims, int dtype, const
             int S = 1;
             while (tiles * S < 512 && rows % (2 * (size_t)S) == 0 && rows / (2 * (size_t)S) >= 256) S *= 2;
             lo.splits.push_back(S);
+            const int Sh = (t > 1 && lo.conv_implicit) ? conv_wgrad_halo_splits(P, B, cv.H, cv.W, cv.ch[t - 1], cv.ch[t]) : 0;
+            lo.splits_halo.push_back(Sh);
+            if (Sh > S) S = Sh;                                          // (sizes the partial buffers below)
             const size_t nw = (size_t)cv.ch[t] * 9 * cv.ch[t - 1];
             if ((size_t)P * S * nw * 4 > partial) partial = (size_t)P * S * nw * 4;
             if ((size_t)P * S * cv.ch[t] * 4 > pbias) pbias = (size_t)P * S * cv.ch[t] * 4;
@@ -800,7 +805,12 @@ int issue_steps_conv(kavg_ctx* c) {
                     KAVG_HIP(c, bf16_conv_backward_data(v, st));
                 }
                 Bracket br(c, KAVG_CLASS_UPDATE);
-                KAVG_HIP(c, bf16_conv_update_partial(v, st));
+                if (lo.splits_halo[t - 1] > 0) {
+                    v.splits = lo.splits_halo[t - 1];
+                    KAVG_HIP(c, conv_wgrad_halo(v, st));
+                } else {
+                    KAVG_HIP(c, bf16_conv_update_partial(v, st));
+                }
                 KAVG_HIP(c, launch_conv_step(v.ws, v.wlo, (uint16_t*)v.bhi, (uint16_t*)v.blo, lo.stride, v.partial, v.partial_bias,
                                              P, v.splits, v.c_out * 9 * v.c_in, v.c_out, c->lr, st));
                 continue;

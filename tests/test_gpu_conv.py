@@ -79,6 +79,11 @@ CASES = [
     (2, 2, 12, 7, 9, (8, 24, 16, 32), (32, 48, 24)),    # three convolutions, 24 classes (generic last layer)
     (2, 2, 32, 16, 16, (8, 32, 64), (64, 10)),          # 8192 positions per learner: the weight gradient is split
     (1, 2, 2, 128, 128, (8, 16, 8), (8, 10)),           # 2^14 positions per image: every convolution on explicit patches
+    # images 32 pixels wide: the weight gradients of convolutions 2.. come from the all-taps kernel
+    (2, 2, 8, 32, 32, (8, 32, 64, 128), (128, 10)),     # the shapes of the cifar_conv workload: 32->64 and 64->128
+    (3, 1, 4, 6, 32, (8, 32, 32), (32, 10)),            # three slices per image, one image per workgroup: borders everywhere
+    (2, 1, 6, 4, 32, (8, 64, 64, 32), (32, 10)),        # three images per workgroup; 64->64 and 64->32
+    (2, 1, 4, 8, 32, (8, 32, 128), (128, 10)),          # 32->128
 ]
 
 
