@@ -13,6 +13,7 @@
 #include "../../include/kavg.h"
 #include "kavg_internal.h"
 #include "conv_wgrad.h"
+#include "conv_direct.h"
 #include "split.h"
 
 using namespace kavg;
@@ -750,7 +751,8 @@ int issue_steps_conv(kavg_ctx* c) {
         for (int t = 1; t <= M; ++t) {                              // convolutions, forward
             Bracket br(c, KAVG_CLASS_FORWARD);
             if (t > 1 && lo.conv_implicit) {
-                KAVG_HIP(c, bf16_conv_forward(implicit_call(t), st));
+                if (conv_direct_ok(H, W, cv.ch[t - 1], cv.ch[t], false)) KAVG_HIP(c, conv_direct_forward(implicit_call(t), st));
+                else KAVG_HIP(c, bf16_conv_forward(implicit_call(t), st));
                 continue;
             }
             if (t == 1)
@@ -800,9 +802,13 @@ int issue_steps_conv(kavg_ctx* c) {
                 ConvCall v = implicit_call(t);
                 {
                     Bracket br(c, KAVG_CLASS_BACKWARD);
-                    KAVG_HIP(c, launch_rotate_weights(v.ws, lo.stride, (uint16_t*)(c->ws + lo.off_wrot), v.wrot_stride, P,
-                                                      v.c_out, v.c_in, st));
-                    KAVG_HIP(c, bf16_conv_backward_data(v, st));
+                    if (conv_direct_ok(H, W, v.c_in, v.c_out, true)) {
+                        KAVG_HIP(c, conv_direct_backward_data(v, st));
+                    } else {
+                        KAVG_HIP(c, launch_rotate_weights(v.ws, lo.stride, (uint16_t*)(c->ws + lo.off_wrot), v.wrot_stride, P,
+                                                          v.c_out, v.c_in, st));
+                        KAVG_HIP(c, bf16_conv_backward_data(v, st));
+                    }
                 }
                 Bracket br(c, KAVG_CLASS_UPDATE);
                 if (lo.splits_halo[t - 1] > 0) {

@@ -84,6 +84,9 @@ CASES = [
     (3, 1, 4, 6, 32, (8, 32, 32), (32, 10)),            # three slices per image, one image per workgroup: borders everywhere
     (2, 1, 6, 4, 32, (8, 64, 64, 32), (32, 10)),        # three images per workgroup; 64->64 and 64->32
     (2, 1, 4, 8, 32, (8, 32, 128), (128, 10)),          # 32->128
+    # ... and, with heights that are multiples of 8, their forward pass and data gradient from the tile kernels
+    (2, 1, 3, 8, 32, (8, 32, 32, 64, 64, 32), (32, 10)),  # 32->32, 32->64, 64->64, 64->32: every remaining channel pairing
+    (1, 2, 2, 16, 32, (8, 128, 32), (32, 10)),          # 128 contraction channels forward: two channel groups
 ]
 
 
