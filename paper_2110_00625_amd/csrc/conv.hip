@@ -26,6 +26,7 @@
 // Between the last convolution and the MLP sits the mean over the H*W positions.
 #include "kavg_internal.h"
 #include "split.h"
+#include "conv_pool.h"
 
 namespace kavg {
 
@@ -139,13 +140,7 @@ pool_backward_kernel(const uint16_t* __restrict__ dpool, const uint16_t* __restr
     const size_t img = e / c8 / HW;
     const u32x4 g = *(const u32x4*)(dpool + img * c + cc * 8);
     const u32x4 m = *(const u32x4*)(act + e * 8);
-    u32x4 o;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const float g0 = __builtin_bit_cast(float, g[q] << 16) * inv, g1 = __builtin_bit_cast(float, g[q] & 0xFFFF0000u) * inv;
-        o[q] = pack2((m[q] & 0x7FFFu) ? g0 : 0.f, (m[q] & 0x7FFF0000u) ? g1 : 0.f);
-    }
-    *(u32x4*)(dz + e * 8) = o;
+    *(u32x4*)(dz + e * 8) = pool_grad_piece(m, g, inv);
 }
 
 // W[j][e] -= lr * sum_s partial[(j*S+s)][e]  and  b[j][r] -= lr * sum_s pbias[(j*S+s)][r]  on the master's planes

@@ -20,6 +20,7 @@
 #include "kavg_internal.h"
 #include "conv_direct.h"
 #include "split.h"
+#include "conv_pool.h"
 #include <type_traits>
 
 namespace kavg {
@@ -60,6 +61,9 @@ struct DirectArgs {
     const uint16_t* act;                                 // data gradient: activations of the layer below (CN channels, same strides as out)
     uint16_t* out; size_t out_lstride;
     int H, tiles;                                        // tiles (of 8 rows) per learner
+    // data gradient of the last convolution: dpool != null means `in` holds that layer's activations and the
+    // gradient images are formed from them and dpool[learner][image][c_k] while loading (conv_pool.h)
+    const uint16_t* dpool; size_t dpool_lstride; float inv;
 };
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
@@ -77,7 +81,8 @@ __device__ __forceinline__ bf16x8 frag_tr(const uint16_t* tile, int pitch, int r
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
-template <int CK, int CN, bool BWD>
+// POOL (data gradient only): the gradient images are formed from activations and dpool while the tile is loaded
+template <int CK, int CN, bool BWD, bool POOL = false>
 __global__ void __launch_bounds__(NT, 4) conv_direct_kernel(DirectArgs a) {
     typedef DirectShape<CK, CN, BWD> SH;
     constexpr int IP = SH::IP, WP = SH::WP, NB = SH::NB;
@@ -124,7 +129,14 @@ __global__ void __launch_bounds__(NT, 4) conv_direct_kernel(DirectArgs a) {
     };
     // the tile's rows row0 - 1 .. row0 + 8 of channel group g: global -> registers -> LDS
     auto load_tile = [&](int g) {
-        u32x4 v[SH::INN];
+        u32x4 v[SH::INN], gp[POOL ? SH::INN : 1];
+        if constexpr (POOL) {                    // requested first, all at once
+#pragma unroll
+            for (int i = 0; i < SH::INN; ++i) {
+                const int e = min(tid + NT * i, SH::IN_PIECES - 1);
+                gp[i] = *(const u32x4*)(a.dpool + (size_t)learner * a.dpool_lstride + (size_t)b * a.c_k + g * CK + (e % (CK / 8)) * 8);
+            }
+        }
 #pragma unroll
         for (int i = 0; i < SH::INN; ++i) {
             const int e = min(tid + NT * i, SH::IN_PIECES - 1);
@@ -134,7 +146,11 @@ __global__ void __launch_bounds__(NT, 4) conv_direct_kernel(DirectArgs a) {
             const bool ok = h >= 0 && h < H;
             const u32x4 x = *(const u32x4*)(in + ((size_t)(ok ? h : row0) * IMG_W + px) * a.c_k + g * CK + ch8 * 8);
             const u32x4 zero = {0u, 0u, 0u, 0u};
-            v[i] = ok ? x : zero;
+            v[i] = ok ? x : zero;                // (zero activations give a zero gradient below)
+        }
+        if constexpr (POOL) {
+#pragma unroll
+            for (int i = 0; i < SH::INN; ++i) v[i] = pool_grad_piece(v[i], gp[i], a.inv);
         }
 #pragma unroll
         for (int i = 0; i < SH::INN; ++i) {
@@ -227,17 +243,17 @@ __global__ void __launch_bounds__(NT, 4) conv_direct_kernel(DirectArgs a) {
     }
 }
 
-template <int CK, int CN, bool BWD>
+template <int CK, int CN, bool BWD, bool POOL = false>
 hipError_t launch_direct(const DirectArgs& a, int P, hipStream_t st) {
     typedef DirectShape<CK, CN, BWD> SH;
     static_assert(2 * SH::SMEM <= 160 * 1024, "two workgroups per compute unit");
     static_assert(ROWS * 32 * OPITCH * 2 <= SH::IN_ELEMS * 2, "output patches fit the tile's LDS");
     if (SH::SMEM > 64 * 1024) {
-        static hipError_t raised = hipFuncSetAttribute((const void*)conv_direct_kernel<CK, CN, BWD>,
+        static hipError_t raised = hipFuncSetAttribute((const void*)conv_direct_kernel<CK, CN, BWD, POOL>,
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, SH::SMEM);
         if (raised != hipSuccess) return raised;
     }
-    hipLaunchKernelGGL((conv_direct_kernel<CK, CN, BWD>), dim3(P * a.tiles), dim3(NT), SH::SMEM, st, a);
+    hipLaunchKernelGGL((conv_direct_kernel<CK, CN, BWD, POOL>), dim3(P * a.tiles), dim3(NT), SH::SMEM, st, a);
     return hipGetLastError();
 }
 
@@ -271,15 +287,25 @@ hipError_t conv_direct_forward(const ConvCall& c, hipStream_t st) {
     return launch_direct<64, 128, false>(a, c.P, st);
 }
 
-hipError_t conv_direct_backward_data(const ConvCall& c, hipStream_t st) {
+hipError_t conv_direct_backward_data(const ConvCall& c, const void* dpool, hipStream_t st) {
     if (!shape_ok(c) || !conv_direct_ok(c.H, c.W, c.c_in, c.c_out, true)) return hipErrorInvalidValue;
     const size_t rows = (size_t)c.B * c.H * c.W;
     DirectArgs a = {};
-    a.in = (const uint16_t*)c.dz; a.in_lstride = rows * c.c_out; a.c_k = c.c_out;
+    if (dpool && !c.out) return hipErrorInvalidValue;
+    a.in = (const uint16_t*)(dpool ? c.out : c.dz); a.in_lstride = rows * c.c_out; a.c_k = c.c_out;
+    a.dpool = (const uint16_t*)dpool; a.dpool_lstride = (size_t)c.B * c.c_out; a.inv = 1.0f / (float)(c.H * c.W);
     a.w = c.ws; a.w_lstride = c.ws_stride;
     a.act = (const uint16_t*)c.in;
     a.out = (uint16_t*)c.dz_in; a.out_lstride = rows * c.c_in;
     a.H = c.H; a.tiles = c.B * (c.H / ROWS);
+    if (dpool) {
+        if (c.c_out == 32) {
+            if (c.c_in == 32) return launch_direct<32, 32, true, true>(a, c.P, st);
+            return launch_direct<32, 64, true, true>(a, c.P, st);
+        }
+        if (c.c_in == 32) return launch_direct<64, 32, true, true>(a, c.P, st);
+        return launch_direct<64, 64, true, true>(a, c.P, st);
+    }
     if (c.c_out == 32) {
         if (c.c_in == 32) return launch_direct<32, 32, true>(a, c.P, st);
         return launch_direct<32, 64, true>(a, c.P, st);

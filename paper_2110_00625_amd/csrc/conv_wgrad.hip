@@ -19,6 +19,7 @@
 // to partial_bias, which conv_step_kernel adds up and applies to the master.
 #include "kavg_internal.h"
 #include "conv_wgrad.h"
+#include "conv_pool.h"
 
 namespace kavg {
 
@@ -49,6 +50,9 @@ struct WgradArgs {
     const uint16_t* in; size_t in_lstride;       // [learner][B*H*W][C_IN]
     float* partial; float* partial_bias;
     int H, images, splits;                       // images per workgroup; ranges per learner
+    // dpool != null: dz holds this layer's activations, and the gradient is formed from them and
+    // dpool[learner][image][C_OUT] while loading (conv_pool.h)
+    const uint16_t* dpool; size_t dpool_lstride; float inv;
 };
 
 // Fragment of a [position][channel] LDS tile for one 16-position slab: lane l receives channel x0 + l%32 at
@@ -63,7 +67,10 @@ __device__ __forceinline__ bf16x8 frag_tr(const uint16_t* tile, int pitch, int r
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
-template <int C_IN, int C_OUT>
+constexpr int POOL_IMAGES_MAX = 64;          // images of a workgroup whose dpool rows are kept in LDS
+
+// POOL: dZ is formed from the layer's activations and dpool while the slice is written to LDS
+template <int C_IN, int C_OUT, bool POOL>
 __global__ void __launch_bounds__(64 * 3 * (C_OUT / 32)) conv_wgrad_halo_kernel(WgradArgs a) {
     typedef WgradShape<C_IN, C_OUT> SH;
     constexpr int OB = SH::OB, NB = SH::NB, NT = SH::NT, ZP = SH::ZP, AP = SH::AP;
@@ -85,6 +92,12 @@ __global__ void __launch_bounds__(64 * 3 * (C_OUT / 32)) conv_wgrad_halo_kernel(
         *(u32x4*)(lds + b * SH::BUF + SH::Z_ELEMS + (row * HALO_W + side * (HALO_W - 1)) * AP + ch8 * 8) = zero;
     }
 
+    // the dpool rows of this workgroup's images: behind the two slice buffers
+    uint16_t* const gl = lds + 2 * SH::BUF;
+    if constexpr (POOL) {
+        const uint16_t* dpool = a.dpool + (size_t)learner * a.dpool_lstride + (size_t)range * a.images * C_OUT;
+        for (int e = tid; e < a.images * (C_OUT / 8); e += NT) *(u32x4*)(gl + e * 8) = *(const u32x4*)(dpool + (size_t)e * 8);
+    }
     u32x4 zr[SH::ZN], ar[SH::AN];
     unsigned a_ok = 0;                           // bit i: piece i of the halo in the registers lies inside the image
     auto fetch = [&](int s) {
@@ -106,13 +119,18 @@ __global__ void __launch_bounds__(64 * 3 * (C_OUT / 32)) conv_wgrad_halo_kernel(
             ar[i] = *(const u32x4*)(in + (((size_t)b * H + (ok ? h : h0)) * IMG_W) * C_IN + (size_t)rest * 8);
         }
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](int buf, int s) {           // s: the slice in the registers
+        const int b = s / half;
         uint16_t* Z = lds + buf * SH::BUF;
         uint16_t* A = Z + SH::Z_ELEMS;
 #pragma unroll
         for (int i = 0; i < SH::ZN; ++i) {
             const int e = tid + NT * i;
-            if (e < SH::Z_PIECES) *(u32x4*)(Z + (e / (C_OUT / 8)) * ZP + (e % (C_OUT / 8)) * 8) = zr[i];
+            if (e < SH::Z_PIECES) {
+                u32x4 v = zr[i];
+                if constexpr (POOL) v = pool_grad_piece(v, *(const u32x4*)(gl + b * C_OUT + (e % (C_OUT / 8)) * 8), a.inv);
+                *(u32x4*)(Z + (e / (C_OUT / 8)) * ZP + (e % (C_OUT / 8)) * 8) = v;
+            }
         }
 #pragma unroll
         for (int i = 0; i < SH::AN; ++i) {
@@ -140,7 +158,8 @@ __global__ void __launch_bounds__(64 * 3 * (C_OUT / 32)) conv_wgrad_halo_kernel(
     float bias_sum = 0.f;
 
     fetch(0);
-    stash(0);
+    if constexpr (POOL) __syncthreads();         // the dpool rows are in LDS
+    stash(0, 0);
     __syncthreads();
     for (int s = 0; s < slices; ++s) {
         const int buf = s & 1;
@@ -166,7 +185,7 @@ __global__ void __launch_bounds__(64 * 3 * (C_OUT / 32)) conv_wgrad_halo_kernel(
 #pragma unroll
         for (int k = 0; k < SLP; k += 6)
             if (k + bg < SLP) bias_sum += __builtin_bit_cast(float, (uint32_t)Z[(k + bg) * ZP + bch] << 16);
-        if (s + 1 < slices) stash(buf ^ 1);      // the other buffer: last read before the previous barrier
+        if (s + 1 < slices) stash(buf ^ 1, s + 1);   // the other buffer: last read before the previous barrier
         __syncthreads();
     }
 
@@ -192,21 +211,28 @@ __global__ void __launch_bounds__(64 * 3 * (C_OUT / 32)) conv_wgrad_halo_kernel(
     }
 }
 
-template <int C_IN, int C_OUT>
-hipError_t launch_wgrad(const WgradArgs& a, int P, hipStream_t st) {
+template <int C_IN, int C_OUT, bool POOL>
+hipError_t launch_wgrad_as(const WgradArgs& a, int P, hipStream_t st) {
     typedef WgradShape<C_IN, C_OUT> SH;
-    static_assert(SH::SMEM <= 160 * 1024, "more LDS than a compute unit has");
+    constexpr int SMEM = SH::SMEM + (POOL ? POOL_IMAGES_MAX * C_OUT * 2 : 0);
+    static_assert(SMEM <= 160 * 1024, "more LDS than a compute unit has");
     static_assert(3 * SH::NB * 16 <= 96, "accumulators leave room for three wavefronts per SIMD");
-    if (SH::SMEM > 64 * 1024) {
-        static hipError_t raised = hipFuncSetAttribute((const void*)conv_wgrad_halo_kernel<C_IN, C_OUT>,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, SH::SMEM);
+    if (SMEM > 64 * 1024) {
+        static hipError_t raised = hipFuncSetAttribute((const void*)conv_wgrad_halo_kernel<C_IN, C_OUT, POOL>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
         if (raised != hipSuccess) return raised;
     }
-    hipLaunchKernelGGL((conv_wgrad_halo_kernel<C_IN, C_OUT>), dim3(P * a.splits), dim3(SH::NT), SH::SMEM, st, a);
+    hipLaunchKernelGGL((conv_wgrad_halo_kernel<C_IN, C_OUT, POOL>), dim3(P * a.splits), dim3(SH::NT), SMEM, st, a);
     return hipGetLastError();
+}
+template <int C_IN, int C_OUT>
+hipError_t launch_wgrad(const WgradArgs& a, int P, hipStream_t st) {
+    return a.dpool ? launch_wgrad_as<C_IN, C_OUT, true>(a, P, st) : launch_wgrad_as<C_IN, C_OUT, false>(a, P, st);
 }
 
 }  // namespace
+
+int conv_wgrad_halo_pool_images() { return POOL_IMAGES_MAX; }
 
 int conv_wgrad_halo_splits(int P, int B, int H, int W, int c_in, int c_out) {
     if (W != IMG_W || H < 2 || H % 2 != 0 || P < 1 || B < 1) return 0;
@@ -217,16 +243,17 @@ int conv_wgrad_halo_splits(int P, int B, int H, int W, int c_in, int c_out) {
     return S;
 }
 
-hipError_t conv_wgrad_halo(const ConvCall& c, hipStream_t st) {
-    if (conv_wgrad_halo_splits(c.P, c.B, c.H, c.W, c.c_in, c.c_out) == 0 || c.splits < 1 || c.B % c.splits != 0 || !c.partial ||
+hipError_t conv_wgrad_halo(const ConvCall& c, const void* dpool, hipStream_t st) {
+    if (conv_wgrad_halo_splits(c.P, c.B, c.H, c.W, c.c_in, c.c_out) == 0 || c.splits < 1 || c.B % c.splits != 0 || !c.partial || (dpool && (!c.out || c.B / c.splits > POOL_IMAGES_MAX)) ||
         !c.partial_bias)
         return hipErrorInvalidValue;
     WgradArgs a;
     const size_t rows = (size_t)c.B * c.H * c.W;
-    a.dz = (const uint16_t*)c.dz; a.dz_lstride = rows * c.c_out;
+    a.dz = (const uint16_t*)(dpool ? c.out : c.dz); a.dz_lstride = rows * c.c_out;
     a.in = (const uint16_t*)c.in; a.in_lstride = rows * c.c_in;
     a.partial = c.partial; a.partial_bias = c.partial_bias;
     a.H = c.H; a.images = c.B / c.splits; a.splits = c.splits;
+    a.dpool = (const uint16_t*)dpool; a.dpool_lstride = (size_t)c.B * c.c_out; a.inv = 1.0f / (float)(c.H * c.W);
     if (c.c_in == 32) {
         if (c.c_out == 32) return launch_wgrad<32, 32>(a, c.P, st);
         if (c.c_out == 64) return launch_wgrad<32, 64>(a, c.P, st);

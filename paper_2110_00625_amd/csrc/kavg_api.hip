@@ -792,7 +792,13 @@ int issue_steps_conv(kavg_ctx* c) {
             Bracket br(c, KAVG_CLASS_UPDATE);
             KAVG_HIP(c, bf16_update(q, st));
         }
-        {
+        // The gradient of the mean over the positions: written out for the generic kernels; the tile kernels of
+        // the last convolution form it while loading (both of them must be in use, or the buffer is needed).
+        const bool pool_fused = M > 1 && lo.conv_implicit && lo.splits_halo[M - 1] > 0 &&
+                                B / lo.splits_halo[M - 1] <= conv_wgrad_halo_pool_images() &&
+                                conv_direct_ok(H, W, cv.ch[M - 1], cv.ch[M], true);
+        const void* dpool_M = c->ws + lo.off_dpool;
+        if (!pool_fused) {
             Bracket br(c, KAVG_CLASS_BACKWARD);
             KAVG_HIP(c, launch_pool_backward(c->ws + lo.off_dpool, c->ws + lo.off_cact[M - 1], c->ws + lo.off_cdz[M - 1],
                                              P, B, H * W, cv.ch[M], st));
@@ -803,7 +809,7 @@ int issue_steps_conv(kavg_ctx* c) {
                 {
                     Bracket br(c, KAVG_CLASS_BACKWARD);
                     if (conv_direct_ok(H, W, v.c_in, v.c_out, true)) {
-                        KAVG_HIP(c, conv_direct_backward_data(v, st));
+                        KAVG_HIP(c, conv_direct_backward_data(v, (pool_fused && t == M) ? dpool_M : nullptr, st));
                     } else {
                         KAVG_HIP(c, launch_rotate_weights(v.ws, lo.stride, (uint16_t*)(c->ws + lo.off_wrot), v.wrot_stride, P,
                                                           v.c_out, v.c_in, st));
@@ -813,7 +819,7 @@ int issue_steps_conv(kavg_ctx* c) {
                 Bracket br(c, KAVG_CLASS_UPDATE);
                 if (lo.splits_halo[t - 1] > 0) {
                     v.splits = lo.splits_halo[t - 1];
-                    KAVG_HIP(c, conv_wgrad_halo(v, st));
+                    KAVG_HIP(c, conv_wgrad_halo(v, (pool_fused && t == M) ? dpool_M : nullptr, st));
                 } else {
                     KAVG_HIP(c, bf16_conv_update_partial(v, st));
                 }
