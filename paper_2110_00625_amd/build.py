@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkavg.so")
-SOURCES = ["kavg_api.hip", "meta_update.hip", "sampling_loss.hip", "gemm_f32.hip", "gemm_bf16.hip", "head.hip", "probe.hip", "conv.hip", "conv_wgrad.hip", "conv_direct.hip", "fused_small.hip"]
+SOURCES = ["kavg_api.hip", "meta_update.hip", "sampling_loss.hip", "gemm_f32.hip", "gemm_bf16.hip", "head.hip", "probe.hip", "conv.hip", "conv_wgrad.hip", "conv_direct.hip", "conv_first.hip", "fused_small.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall",
          # keep the compiler from forming packed fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -14,6 +14,7 @@
 #include "kavg_internal.h"
 #include "conv_wgrad.h"
 #include "conv_direct.h"
+#include "conv_first.h"
 #include "split.h"
 
 using namespace kavg;
@@ -120,7 +121,10 @@ Layout make_layout(int P, int K, int B, int L, const int* dims, int dtype, const
         size_t draw = 0, partial = 0, pbias = 0, wrot = 0;
         lo.conv_implicit = (size_t)cv.H * cv.W < ((size_t)1 << 14);     // range of the loaders' multiply-shift divisions
         for (int t = 1; t <= M; ++t) {
-            const bool expl = t == 1 || !lo.conv_implicit;             // the first convolution gathers its images: explicit patches
+            const int S1 = (t == 1 && lo.conv_implicit) ? conv_first_splits(P, B, cv.H, cv.W, cv.ch[0], cv.ch[1]) : 0;
+            // explicit patches: every convolution of very large images, and a first convolution (it gathers its images)
+            // that the kernels of conv_first.hip do not cover
+            const bool expl = (t == 1 && S1 == 0) || !lo.conv_implicit;
             lo.off_patch.push_back(expl ? take((size_t)P * rows * 9 * cv.ch[t - 1] * 2) : 0);
             lo.off_cact.push_back(take((size_t)P * rows * cv.ch[t] * 2));
             lo.off_cdz.push_back(take((size_t)P * rows * cv.ch[t] * 2));
@@ -132,7 +136,7 @@ Layout make_layout(int P, int K, int B, int L, const int* dims, int dtype, const
             int S = 1;
             while (tiles * S < 512 && rows % (2 * (size_t)S) == 0 && rows / (2 * (size_t)S) >= 256) S *= 2;
             lo.splits.push_back(S);
-            const int Sh = (t > 1 && lo.conv_implicit) ? conv_wgrad_halo_splits(P, B, cv.H, cv.W, cv.ch[t - 1], cv.ch[t]) : 0;
+            const int Sh = t == 1 ? S1 : lo.conv_implicit ? conv_wgrad_halo_splits(P, B, cv.H, cv.W, cv.ch[t - 1], cv.ch[t]) : 0;
             lo.splits_halo.push_back(Sh);
             if (Sh > S) S = Sh;                                          // (sizes the partial buffers below)
             const size_t nw = (size_t)cv.ch[t] * 9 * cv.ch[t - 1];
@@ -744,12 +748,27 @@ int issue_steps_conv(kavg_ctx* c) {
         v.splits = lo.splits[t - 1];
         return v;
     };
+    const bool first_direct = lo.conv_implicit && lo.splits_halo[0] > 0;   // the first convolution straight from the gathered images
+    auto first_call = [&]() {
+        ConvCall v{};
+        v.P = P; v.B = B; v.H = H; v.W = W; v.c_in = cv.ch[0]; v.c_out = cv.ch[1];
+        v.ws = c->hi_planes() + lo.cw_off[0]; v.wlo = c->lo_planes() + lo.cw_off[0]; v.ws_stride = lo.stride;
+        v.bhi = c->hi_planes() + lo.cb_off[0]; v.blo = c->lo_planes() + lo.cb_off[0];
+        v.out = c->ws + lo.off_cact[0]; v.dz = c->ws + lo.off_cdz[0];
+        v.partial = (float*)(c->ws + lo.off_partial); v.partial_bias = (float*)(c->ws + lo.off_pbias);
+        v.splits = lo.splits_halo[0];
+        return v;
+    };
     for (int k = 0; k < c->K; ++k) {
         const int32_t* idx_k = c->idx() + (size_t)k * B;
         const long idx_ls = (long)c->K * B;
         float* rowloss_k = c->rowloss() + (size_t)k * P * B;
         for (int t = 1; t <= M; ++t) {                              // convolutions, forward
             Bracket br(c, KAVG_CLASS_FORWARD);
+            if (t == 1 && first_direct) {
+                KAVG_HIP(c, conv_first_forward(first_call(), c->X, idx_k, idx_ls, st));
+                continue;
+            }
             if (t > 1 && lo.conv_implicit) {
                 if (conv_direct_ok(H, W, cv.ch[t - 1], cv.ch[t], false)) KAVG_HIP(c, conv_direct_forward(implicit_call(t), st));
                 else KAVG_HIP(c, bf16_conv_forward(implicit_call(t), st));
@@ -823,6 +842,14 @@ int issue_steps_conv(kavg_ctx* c) {
                 } else {
                     KAVG_HIP(c, bf16_conv_update_partial(v, st));
                 }
+                KAVG_HIP(c, launch_conv_step(v.ws, v.wlo, (uint16_t*)v.bhi, (uint16_t*)v.blo, lo.stride, v.partial, v.partial_bias,
+                                             P, v.splits, v.c_out * 9 * v.c_in, v.c_out, c->lr, st));
+                continue;
+            }
+            if (t == 1 && first_direct) {
+                Bracket br(c, KAVG_CLASS_UPDATE);
+                ConvCall v = first_call();
+                KAVG_HIP(c, conv_first_wgrad(v, c->X, idx_k, idx_ls, st));
                 KAVG_HIP(c, launch_conv_step(v.ws, v.wlo, (uint16_t*)v.bhi, (uint16_t*)v.blo, lo.stride, v.partial, v.partial_bias,
                                              P, v.splits, v.c_out * 9 * v.c_in, v.c_out, c->lr, st));
                 continue;

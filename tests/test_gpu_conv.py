@@ -87,6 +87,7 @@ CASES = [
     # ... and, with heights that are multiples of 8, their forward pass and data gradient from the tile kernels
     (2, 1, 3, 8, 32, (8, 32, 32, 64, 64, 32), (32, 10)),  # 32->32, 32->64, 64->64, 64->32: every remaining channel pairing
     (1, 2, 2, 16, 32, (8, 128, 32), (32, 10)),          # 128 contraction channels forward: two channel groups
+    (2, 2, 4, 8, 32, (8, 64, 32), (32, 10)),            # first convolution 8->64 straight from the gathered images (8->32: above)
 ]
 
 
