@@ -8,8 +8,9 @@
 // (dx+1)).  The generic kernel forms the patch matrix in its operand loaders, which reads every input
 // pixel nine times out of L2; here a workgroup owns eight image rows (256 positions) and all output
 // channels, loads those rows plus one above and one below (a zero pixel on either side) into LDS, and
-// every tap reads the same tile at a shifted pixel.  Only the weights still stream per tap (one slice of
-// [channels out][channels in] per tap, single LDS buffer, the next slice waiting in registers).
+// every tap reads the same tile at a shifted pixel.  Only the weights still stream: one slice of
+// [channels out][channels in] per tap, one to three taps per step (as many as leave LDS for two workgroups
+// per compute unit), single LDS buffer, the slices of the next two steps waiting in registers.
 //
 // Eight wavefronts, one per image row: wavefront w holds the 32 positions of row w times all N output
 // channels (N/32 accumulator blocks).  MFMA 32x32x16 bf16 with the weights as the first operand
@@ -47,8 +48,11 @@ struct DirectShape {
     static constexpr int IN_ELEMS = HALO_PX * IP;
     static constexpr int WP = BWD ? CN + 32 : CK + 8;            // weight slice rows: [k][n] for the data gradient (transpose reads), [n][k] forward
     static constexpr int W_ROWS = BWD ? CK : CN, W_COLS = BWD ? CN : CK;
-    static constexpr int W_ELEMS = W_ROWS * WP;
-    static constexpr int SMEM = (IN_ELEMS + W_ELEMS) * 2;
+    static constexpr int W_ELEMS = W_ROWS * WP;                  // one tap's slice
+    // taps per step (one weight buffer, two barriers per step): as many as leave room for two workgroups per compute unit
+    static constexpr int TPS = 2 * (IN_ELEMS + 3 * W_ELEMS) * 2 <= 160 * 1024 ? 3 : 2 * (IN_ELEMS + 2 * W_ELEMS) * 2 <= 160 * 1024 ? 2 : 1;
+    static constexpr int STEPS = (9 + TPS - 1) / TPS;            // per channel group
+    static constexpr int SMEM = (IN_ELEMS + TPS * W_ELEMS) * 2;
     static constexpr int W_PIECES = W_ROWS * W_COLS / 8, WN = (W_PIECES + NT - 1) / NT;
     static constexpr int IN_PIECES = (ROWS + 2) * IMG_W * CK / 8, INN = (IN_PIECES + NT - 1) / NT;
     static constexpr int NB = CN / 32;
@@ -108,24 +112,32 @@ __global__ void __launch_bounds__(NT, 4) conv_direct_kernel(DirectArgs a) {
     // weight slice of (group g, tap): forward [n = o][k = c of the group], data gradient [k = o of the group][n = c]
     // Two slices wait in registers (sets 0 and 1 in turn): a slice is requested two taps before it is used,
     // which is about what a read out of L2 takes.
-    u32x4 wr[2][SH::WN];
-    auto wfetch = [&](auto set, int s) {
-        const int g = s / 9, tap = s - g * 9;
+    constexpr int TPS = SH::TPS, STEPS = SH::STEPS;
+    u32x4 wr[2][TPS][SH::WN];
+    auto wfetch = [&](auto set, int s) {         // step s = (group, taps TPS*st .. ), taps beyond the ninth clamped (never used)
+        const int g = s / STEPS, tap0 = (s - g * STEPS) * TPS;
 #pragma unroll
-        for (int i = 0; i < SH::WN; ++i) {
-            const int e = min(tid + NT * i, SH::W_PIECES - 1);
-            const int r = e / (SH::W_COLS / 8), c8 = e - r * (SH::W_COLS / 8);
-            const int o = BWD ? g * CK + r : r;
-            const int c = BWD ? c8 * 8 : g * CK + c8 * 8;
-            wr[set][i] = *(const u32x4*)(w + ((size_t)o * 9 + tap) * c_in + c);
+        for (int tt = 0; tt < TPS; ++tt) {
+            const int tap = min(tap0 + tt, 8);
+#pragma unroll
+            for (int i = 0; i < SH::WN; ++i) {
+                const int e = min(tid + NT * i, SH::W_PIECES - 1);
+                const int r = e / (SH::W_COLS / 8), c8 = e - r * (SH::W_COLS / 8);
+                const int o = BWD ? g * CK + r : r;
+                const int c = BWD ? c8 * 8 : g * CK + c8 * 8;
+                wr[set][tt][i] = *(const u32x4*)(w + ((size_t)o * 9 + tap) * c_in + c);
+            }
         }
     };
     auto wstash = [&](auto set) {
 #pragma unroll
-        for (int i = 0; i < SH::WN; ++i) {
-            const int e = tid + NT * i;
-            if (e < SH::W_PIECES) *(u32x4*)(WT + (e / (SH::W_COLS / 8)) * WP + (e % (SH::W_COLS / 8)) * 8) = wr[set][i];
-        }
+        for (int tt = 0; tt < TPS; ++tt)
+#pragma unroll
+            for (int i = 0; i < SH::WN; ++i) {
+                const int e = tid + NT * i;
+                if (e < SH::W_PIECES)
+                    *(u32x4*)(WT + tt * SH::W_ELEMS + (e / (SH::W_COLS / 8)) * WP + (e % (SH::W_COLS / 8)) * 8) = wr[set][tt][i];
+            }
     };
     // the tile's rows row0 - 1 .. row0 + 8 of channel group g: global -> registers -> LDS
     auto load_tile = [&](int g) {
@@ -169,34 +181,41 @@ __global__ void __launch_bounds__(NT, 4) conv_direct_kernel(DirectArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
 
-    const int steps = 9 * groups;                // (channel group, tap) pairs, in order
+    const int steps = STEPS * groups;            // (channel group, TPS taps) in order
     auto step = [&](auto set, int s) {
-        const int g = s / 9, tap = s - g * 9;
-        if (tap == 0) load_tile(g);              // (the previous group's last tap ended with a barrier)
+        const int g = s / STEPS, tap0 = (s - g * STEPS) * TPS;
+        if (tap0 == 0) load_tile(g);             // (the previous group's last step ended with a barrier)
         wstash(set);
-        __syncthreads();                         // the slice (and, at tap 0, the tile) is in LDS
+        __syncthreads();                         // the slices (and, at the group's first step, the tile) are in LDS
         if (s + 2 < steps) wfetch(set, s + 2);
-        const int dy = tap / 3 - 1, dx = tap - (tap / 3) * 3 - 1;
-        // pixel this lane's position reads for the tap: forward p + (dy, dx), data gradient p - (dy, dx)
-        const int pix = (wave + 1 + (BWD ? -dy : dy)) * HALO_W + (lane & 31) + 1 + (BWD ? -dx : dx);
-        const uint16_t* ip = IN + pix * IP + (lane >> 5) * 8;
 #pragma unroll
-        for (int kq = 0; kq < CK / 16; ++kq) {
-            const bf16x8 xf = *(const bf16x8*)(ip + kq * 16);
+        for (int tt = 0; tt < TPS; ++tt) {
+            const int tap = tap0 + tt;
+            if (tap < 9) {
+                const int dy = tap / 3 - 1, dx = tap - (tap / 3) * 3 - 1;
+                // pixel this lane's position reads for the tap: forward p + (dy, dx), data gradient p - (dy, dx)
+                const int pix = (wave + 1 + (BWD ? -dy : dy)) * HALO_W + (lane & 31) + 1 + (BWD ? -dx : dx);
+                const uint16_t* ip = IN + pix * IP + (lane >> 5) * 8;
+                const uint16_t* wt = WT + tt * SH::W_ELEMS;
 #pragma unroll
-            for (int j = 0; j < NB; ++j) {
-                bf16x8 wf;
-                if constexpr (BWD) wf = frag_tr(WT, WP, kq * 16, j * 32, lane);
-                else wf = *(const bf16x8*)(WT + (j * 32 + (lane & 31)) * WP + kq * 16 + (lane >> 5) * 8);
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[j], 0, 0, 0);
+                for (int kq = 0; kq < CK / 16; ++kq) {
+                    const bf16x8 xf = *(const bf16x8*)(ip + kq * 16);
+#pragma unroll
+                    for (int j = 0; j < NB; ++j) {
+                        bf16x8 wf;
+                        if constexpr (BWD) wf = frag_tr(wt, WP, kq * 16, j * 32, lane);
+                        else wf = *(const bf16x8*)(wt + (j * 32 + (lane & 31)) * WP + kq * 16 + (lane >> 5) * 8);
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[j], 0, 0, 0);
+                    }
+                }
             }
         }
-        __syncthreads();                         // everyone is done with the slice (and, after the last tap, with the tile)
+        __syncthreads();                         // everyone is done with the slices (and, after the last step, with the tile)
     };
     constexpr std::integral_constant<int, 0> set0;
     constexpr std::integral_constant<int, 1> set1;
     wfetch(set0, 0);
-    wfetch(set1, 1);
+    if (steps > 1) wfetch(set1, 1);
     for (int s = 0; s < steps; s += 2) {
         step(set0, s);
         if (s + 1 < steps) step(set1, s + 1);

@@ -10,9 +10,9 @@
 // column on either side) in LDS, and every tap's operand is the same LDS tile read at a shifted pixel.
 // Per 64 positions a compute unit then takes in 16 KB + 16 KB instead of nine times 24 KB.
 //
-// Workgroup = (learner, range of whole images); 3 * c_out/32 wavefronts: wavefront (ob, tl) owns output
-// channels 32 ob .. +31 and the taps with dx = tl - 1 (dy = -1, 0, 1), i.e. 3 * c_in/32 accumulator blocks
-// of 32x32.  MFMA 32x32x16 bf16 with M = output channel, N = input channel, K = position; both operands lie
+// Workgroup = (learner, range of whole images); 3 * c_out/32 wavefronts: a wavefront owns the taps with
+// dx = tl - 1 (dy = -1, 0, 1) for 32 output channels and all input channels (or, see the kernel, 64 output
+// channels and 32 input channels), i.e. 3 * c_in/32 accumulator blocks of 32x32.  MFMA 32x32x16 bf16 with M = output channel, N = input channel, K = position; both operands lie
 // in LDS as [position][channel] and their fragments come from the transpose read, as in the generic update
 // kernel.  Slices are double-buffered in LDS (one barrier per slice), the next one waits in registers.
 // The fp32 sums of a workgroup go to partial[learner * splits + range][o][9 c_in] and the column sums of dZ
@@ -77,7 +77,14 @@ __global__ void __launch_bounds__(64 * 3 * (C_OUT / 32)) conv_wgrad_halo_kernel(
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint16_t* const lds = (uint16_t*)smem;       // buffer b: dZ rows at lds + b*BUF, halo at + Z_ELEMS
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int ob = wave % OB, tl = wave / OB;    // output-channel block; taps with dx = tl - 1
+    // A wavefront owns the taps with dx = tl - 1 and, of the OB x NB blocks (output channels x input channels), either
+    // one output block and all input blocks or -- when there are two input blocks and an even number of output
+    // blocks -- two output blocks and one input block: the same six accumulator blocks, five fragment reads per
+    // slab instead of seven.
+    constexpr bool PAIR = NB == 2 && OB % 2 == 0;
+    constexpr int OI = PAIR ? 2 : 1, NI = PAIR ? 1 : NB;
+    const int tl = wave / OB;
+    const int ob0 = PAIR ? ((wave % OB) >> 1) * 2 : wave % OB, nb0 = PAIR ? (wave % OB) & 1 : 0;
     const int lp = blockIdx.x, learner = lp / a.splits, range = lp - learner * a.splits;
     const int H = a.H, half = H / 2;
     const size_t pos0 = (size_t)range * a.images * H * IMG_W;
@@ -144,13 +151,15 @@ __global__ void __launch_bounds__(64 * 3 * (C_OUT / 32)) conv_wgrad_halo_kernel(
         }
     };
 
-    f32x16 acc[3][NB];
+    f32x16 acc[3][OI][NI];
 #pragma unroll
     for (int ty = 0; ty < 3; ++ty)
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
+        for (int oi = 0; oi < OI; ++oi)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[ty][nb][e] = 0.f;
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[ty][oi][ni][e] = 0.f;
     // column sums of dZ: the workgroup has 6 threads per output channel (NT = 6 C_OUT); thread (g, ch) adds the
     // positions g, g + 6, ... of every slice, and the six partial sums are joined in fixed order at the end
     static_assert(NT == 6 * C_OUT, "six threads per output channel");
@@ -169,16 +178,20 @@ __global__ void __launch_bounds__(64 * 3 * (C_OUT / 32)) conv_wgrad_halo_kernel(
 #pragma unroll
         for (int kq = 0; kq < SLP / 16; ++kq) {
             // slab kq: positions 16 kq .. +15 = image row kq/2 of the slice, pixels 16 (kq%2) .. +15
-            const bf16x8 zf = frag_tr(Z, ZP, kq * 16, ob * 32, lane);
+            bf16x8 zf[OI];
+#pragma unroll
+            for (int oi = 0; oi < OI; ++oi) zf[oi] = frag_tr(Z, ZP, kq * 16, (ob0 + oi) * 32, lane);
             const int r = kq >> 1, w0 = (kq & 1) * 16;
 #pragma unroll
             for (int ty = 0; ty < 3; ++ty) {
                 // tap (dy, dx) = (ty - 1, tl - 1): halo row r + 1 + dy, halo pixel w0 + 1 + dx
                 const int row0 = (r + ty) * HALO_W + w0 + tl;
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const bf16x8 af = frag_tr(A, AP, row0, nb * 32, lane);
-                    acc[ty][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zf, af, acc[ty][nb], 0, 0, 0);
+                for (int ni = 0; ni < NI; ++ni) {
+                    const bf16x8 af = frag_tr(A, AP, row0, (nb0 + ni) * 32, lane);
+#pragma unroll
+                    for (int oi = 0; oi < OI; ++oi)
+                        acc[ty][oi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zf[oi], af, acc[ty][oi][ni], 0, 0, 0);
                 }
             }
         }
@@ -194,12 +207,14 @@ __global__ void __launch_bounds__(64 * 3 * (C_OUT / 32)) conv_wgrad_halo_kernel(
 #pragma unroll
     for (int ty = 0; ty < 3; ++ty)
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
+        for (int oi = 0; oi < OI; ++oi)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int o = ob * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                out[(size_t)o * 9 * C_IN + (ty * 3 + tl) * C_IN + nb * 32 + (lane & 31)] = acc[ty][nb][e];
-            }
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int o = (ob0 + oi) * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                    out[(size_t)o * 9 * C_IN + (ty * 3 + tl) * C_IN + (nb0 + ni) * 32 + (lane & 31)] = acc[ty][oi][ni][e];
+                }
     float* red = (float*)smem;                   // (the tiles are dead: the loop ended with a barrier)
     red[bg * C_OUT + bch] = bias_sum;
     __syncthreads();
