@@ -24,6 +24,10 @@
 // fp32 partial tiles instead of stepping the master), and conv_step_kernel adds the S partials in
 // ascending order and takes the SGD step of Algorithm 1 on the master's two planes (split.h).
 // Between the last convolution and the MLP sits the mean over the H*W positions.
+//
+// Images 32 pixels wide do not take these paths where the tile kernels cover the layer (conv_first.hip,
+// conv_direct.hip, conv_wgrad.hip: the image rows a workgroup needs are held in LDS and every tap reads them
+// at a shifted pixel); what is here serves every other shape, and the pooling and the master step for all.
 #include "kavg_internal.h"
 #include "split.h"
 #include "conv_pool.h"
