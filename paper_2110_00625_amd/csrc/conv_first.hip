@@ -275,8 +275,10 @@ hipError_t launch_first_wgrad(const FirstArgs& a, int P, hipStream_t st) {
 
 int conv_first_splits(int P, int B, int H, int W, int c_in, int c_out) {
     if (W != IMG_W || c_in != CH || H < ROWS || H % ROWS != 0 || P < 1 || B < 1 || !(c_out == 32 || c_out == 64)) return 0;
+    // two workgroups per compute unit where the batch allows: a slice is short, and one workgroup alone would
+    // wait out the latency of every slice's loads
     int S = 1;
-    while (P * S < 256 && B % (2 * S) == 0) S *= 2;
+    while (P * S < 512 && B % (2 * S) == 0) S *= 2;
     return S;
 }
 

@@ -252,9 +252,11 @@ int conv_wgrad_halo_pool_images() { return POOL_IMAGES_MAX; }
 int conv_wgrad_halo_splits(int P, int B, int H, int W, int c_in, int c_out) {
     if (W != IMG_W || H < 2 || H % 2 != 0 || P < 1 || B < 1) return 0;
     if (!(c_in == 32 || c_in == 64) || !(c_out == 32 || c_out == 64 || c_out == 128)) return 0;
-    // ranges of whole images, enough of them for one workgroup per compute unit where the batch allows
+    // ranges of whole images, enough of them for one workgroup per compute unit where the batch allows -- two
+    // where two fit (LDS: up to 64 input and output channels)
+    const int target = (c_in <= 64 && c_out <= 64) ? 512 : 256;
     int S = 1;
-    while (P * S < 256 && B % (2 * S) == 0) S *= 2;
+    while (P * S < target && B % (2 * S) == 0) S *= 2;
     return S;
 }
 
