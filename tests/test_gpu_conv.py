@@ -110,6 +110,24 @@ def test_conv_learner_matches_the_oracle(P, K, B, H, W, channels, dims):
         assert e < TOL_BF16, "global model after round %d: %.3g" % (r, e)
 
 
+def test_cifar_conv_launch_configuration_one_step_sampled_learners():
+    """The benchmark's convolutional workload at its full launch configuration (P = 16 learners of B = 64 images of
+    32x32, channels 8-32-64-128: 256 or 512 image ranges per weight gradient, 4096 tiles per forward pass), one local
+    step; the oracle walks the first and the last learner."""
+    from paper_2110_00625_amd.configs import CIFAR_CONV as w
+    g, o, spec = _setup(w.P, 1, w.B, w.H, w.W, w.channels, w.dims, 73, N=600, lr=w.lr, mu=w.mu)
+    g.local_steps()
+    sample = [0, w.P - 1]
+    o.local_steps(learners=sample)
+    for j in sample:
+        assert np.array_equal(g.indices()[j], o.indices()[j])
+        e = conv_error(g.replica(j), o.replica(j), spec, verbose=True)
+        print("cifar_conv learner %d after one local step: %.3g" % (j, e))
+        assert e < 2e-4, e                 # measured 2e-6 .. 4e-6
+        assert abs(g.losses()[0, j] - o.losses()[0, j]) < 1e-3 * max(1.0, o.losses()[0, j])
+    g.close()
+
+
 def test_conv_first_step_is_tight():
     """One step of one learner from bf16-exact inputs.  The step itself (replica minus start, i.e.
     -lr times the minibatch gradient) is compared tensor by tensor on ITS OWN scale, so a gradient that
