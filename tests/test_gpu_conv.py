@@ -128,6 +128,29 @@ def test_cifar_conv_launch_configuration_one_step_sampled_learners():
     g.close()
 
 
+def test_cifar_conv_whole_round_every_learner():
+    """One whole meta round of the benchmark's convolutional workload (P = 16, K = 8, B = 64), free running from
+    w~_1: every replica after the local steps, the per-step losses, and the global model after the meta step."""
+    from paper_2110_00625_amd.configs import CIFAR_CONV as w
+    g, o, spec = _setup(w.P, w.K, w.B, w.H, w.W, w.channels, w.dims, 74, N=2000, lr=w.lr, mu=w.mu)
+    g.local_steps()
+    o.local_steps(workers=8)
+    assert np.array_equal(g.indices(), o.indices())
+    worst = 0.0
+    for j in range(w.P):
+        worst = max(worst, conv_error(g.replica(j), o.replica(j), spec))
+    print("cifar_conv, replicas after %d local steps: worst %.3g" % (w.K, worst))
+    assert worst < TOL_BF16
+    gl, ol = g.losses(), o.losses()
+    assert np.max(np.abs(gl - ol) / np.maximum(np.abs(ol), 1e-3)) < TOL_BF16
+    g.meta_update()
+    o.meta_update()
+    e = conv_error(g.params(), o.params(), spec, verbose=True)
+    print("cifar_conv, global model after the round: %.3g" % e)
+    assert e < TOL_BF16
+    g.close()
+
+
 def test_conv_first_step_is_tight():
     """One step of one learner from bf16-exact inputs.  The step itself (replica minus start, i.e.
     -lr times the minibatch gradient) is compared tensor by tensor on ITS OWN scale, so a gradient that
