@@ -710,8 +710,11 @@ extern "C++" HistoryLayout history_layout(const kavg_ctx* c, int m) {
 }
 
 // The K local steps of a network whose MLP sits behind a stack of 3x3 convolutions (the CNN workloads
-// of Section 4): per step and convolution the patch matrix is written out, the three products of a
-// dense layer run on it with B*H*W rows, and the mean over the positions joins the two parts.
+// of Section 4).  Per step a convolution is three products on B*H*W rows (forward, data gradient, weight
+// gradient), and the mean over the positions joins the convolutions and the MLP.  Which kernels run them is
+// decided per layer from its shape: the tile kernels for images 32 pixels wide (conv_first.hip,
+// conv_direct.hip, conv_wgrad.hip), else the generic MFMA kernel on the implicit patch matrix, else (first
+// layer, or images of 2^14 positions and more) the same kernel on a patch matrix that is written out.
 int issue_steps_conv(kavg_ctx* c) {
     hipStream_t st = c->stream;
     const Layout& lo = c->lo;
